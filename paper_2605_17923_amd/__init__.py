@@ -1,0 +1,6 @@
+"""MI355X-native fused LayerNorm-Modulate (AdaLN): hand-written gfx950 kernels behind a C ABI.
+
+`lnmod` is the thin binding over the shared library (argument marshalling only);
+`synth` holds the seeded synthetic workloads.
+"""
+from . import synth  # noqa: F401
