@@ -1,0 +1,146 @@
+/*
+ * lnmod.h -- C ABI of the MI355X (gfx950) fused LayerNorm-Modulate (AdaLN) library.
+ *
+ * The operator is the one the paper fuses in Sec. 3.3 ("Fused LayerNorm-Modulate kernels"):
+ * for every token row, mean and variance over the hidden dimension D, normalisation, and the
+ * modulation by the timestep-conditioned shift/scale, in one launch; the statistics are kept in
+ * global memory for the backward pass; the backward pass returns dx and the modulation
+ * gradients reduced along the token axis with fp32 accumulation (Sec. 3.3, Sec. 4.5).
+ * Written out (LayerNorm without affine, biased variance, eps inside the square root):
+ *
+ *     mean_n = (1/D) sum_d x[n,d]            rstd_n = 1/sqrt((1/D) sum_d (x[n,d]-mean_n)^2 + eps)
+ *     xhat   = (x[n,d] - mean_n) * rstd_n    y[n,d] = xhat * (1 + scale[m,d]) + shift[m,d]
+ *     g      = dy[n,d] * (1 + scale[m,d])    c1 = (1/D) sum_d g      c2 = (1/D) sum_d g*xhat
+ *     dx[n,d] = rstd_n * (g - c1 - xhat*c2)
+ *     dshift[m,d] = sum_{n in m} dy[n,d]     dscale[m,d] = sum_{n in m} dy[n,d]*xhat[n,d]
+ *
+ * m is the modulation row of token n: its sample (LNMOD_PER_SAMPLE), its packed segment
+ * (the *_varlen calls) or the token itself (LNMOD_PER_TOKEN, no sum).
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer (memory of the current HIP device) unless the comment
+ *     says "host".  The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and never synchronises: kernels are enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL is the default stream) and the call returns at once.
+ *   - Tensors are dense and row-major with D contiguous: x, y, dy, dx are [N, D], N tokens.
+ *   - `dtype` is the element type of x, y, dy, dx, shift, scale (LNMOD_BF16 or LNMOD_F32).
+ *     All arithmetic is fp32; bf16 results are rounded once, to nearest even, at the store.
+ *     mean, rstd and the reduced dshift/dscale are always float32.
+ *   - Supported D: a multiple of 8 (bf16) or 4 (fp32), 8 <= D <= 8192.  Every tensor pointer
+ *     must be 16-byte aligned.
+ *   - Inputs and outputs must not overlap.  Outputs are overwritten in full; nothing is
+ *     accumulated into them.  Results are bitwise reproducible for equal inputs and shapes.
+ *   - The return value is the only error channel (no exceptions, no abort, nothing printed).
+ *     Arguments are validated before any HIP call, so a bad call enqueues nothing.
+ *       LNMOD_EINVAL        NULL required pointer; negative size; eps not finite or <= 0;
+ *                           unknown dtype or mod; token count at or above 2^31
+ *       LNMOD_EUNSUPPORTED  D outside the supported set
+ *       LNMOD_EALIGN        a tensor pointer is not 16-byte aligned
+ *       LNMOD_EWORKSPACE    workspace NULL or smaller than lnmod_backward_workspace_bytes()
+ *       LNMOD_ELAUNCH       the HIP runtime reported an error for the launch
+ *     N == 0 returns LNMOD_OK; per-sample dshift/dscale of B > 0 samples are then zero-filled.
+ */
+#ifndef LNMOD_H
+#define LNMOD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LNMOD_OK = 0,
+    LNMOD_EINVAL = 1,
+    LNMOD_EUNSUPPORTED = 2,
+    LNMOD_EALIGN = 3,
+    LNMOD_EWORKSPACE = 4,
+    LNMOD_ELAUNCH = 5
+} lnmod_status;
+
+typedef enum { LNMOD_BF16 = 0, LNMOD_F32 = 1 } lnmod_dtype;
+
+typedef enum {
+    LNMOD_PER_SAMPLE = 0, /* shift, scale: [B, D] */
+    LNMOD_PER_TOKEN = 1   /* shift, scale: [B, S, D] */
+} lnmod_mod;
+
+/*
+ * Forward (Sec. 3.3, forward kernel: statistics, normalisation and modulation in one launch,
+ * statistics saved).  x, y: [B*S, D]; shift, scale: [B, D] or [B, S, D] by `mod`;
+ * mean, rstd: float32 [B*S] (written).
+ */
+int lnmod_forward(const void* x, const void* shift, const void* scale,
+                  int64_t B, int64_t S, int64_t D, float eps, void* stream,
+                  void* y, float* mean, float* rstd, int dtype, int mod);
+
+/*
+ * Backward (Sec. 3.3, backward: dx, and dshift/dscale by per-feature accumulation along the
+ * sequence in fp32).  dy, x, dx: [B*S, D]; mean, rstd: what lnmod_forward saved for this x.
+ * `shift` is not needed and may be NULL; `eps` is not needed (rstd is saved) and is only
+ * validated.  LNMOD_PER_SAMPLE: dshift, dscale are float32 [B, D] and `workspace` must hold
+ * lnmod_backward_workspace_bytes(B, B*S, D, mod) bytes (contents need no initialisation and
+ * are garbage afterwards).  LNMOD_PER_TOKEN: dshift, dscale are [B, S, D] in the I/O dtype;
+ * workspace may be NULL.
+ */
+int lnmod_backward(const void* dy, const void* x, const void* shift, const void* scale,
+                   int64_t B, int64_t S, int64_t D, float eps, void* stream,
+                   const float* mean, const float* rstd,
+                   void* dx, void* dshift, void* dscale,
+                   void* workspace, size_t workspace_bytes, int dtype, int mod);
+
+/*
+ * Forward on a packed batch of nseg segments of different lengths (the mixed image/video
+ * batches of Sec. 3.2 laid end to end).  x, y: [T, D]; shift, scale: [nseg, D];
+ * cu_seqlens: device int32 [nseg+1], non-decreasing, cu_seqlens[0] = 0, cu_seqlens[nseg] = T;
+ * zero-length segments are allowed.  The table is read on the device only; a malformed table
+ * gives unspecified values but no out-of-bounds access.  nseg plays B, T plays S.
+ */
+int lnmod_forward_varlen(const void* x, const void* shift, const void* scale,
+                         const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D,
+                         float eps, void* stream,
+                         void* y, float* mean, float* rstd, int dtype);
+
+/*
+ * Backward on a packed batch.  dshift, dscale: float32 [nseg, D]; the rows of zero-length
+ * segments are written as zeros.  workspace: lnmod_backward_workspace_bytes(nseg, T, D,
+ * LNMOD_PER_SAMPLE) bytes.
+ */
+int lnmod_backward_varlen(const void* dy, const void* x, const void* shift, const void* scale,
+                          const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D,
+                          float eps, void* stream,
+                          const float* mean, const float* rstd,
+                          void* dx, void* dshift, void* dscale,
+                          void* workspace, size_t workspace_bytes, int dtype);
+
+/*
+ * Bytes of device workspace the backward needs for its per-block partial sums of
+ * dshift/dscale (Sec. 3.3: per-feature accumulation down the sequence; the partials of the
+ * blocks are combined by a second, fixed-order kernel).  0 for LNMOD_PER_TOKEN and for invalid
+ * arguments.  Host-only, touches no device.
+ */
+size_t lnmod_backward_workspace_bytes(int64_t B_or_nseg, int64_t total_tokens, int64_t D, int mod);
+
+/* Static, NUL-terminated description of a status code (host pointer, never NULL). */
+const char* lnmod_status_string(int status);
+
+/*
+ * Measurement comparators, not part of the fused path.
+ *
+ * lnmod_unfused_forward: the decoupled chain the paper argues against (Sec. 3.3, 3.4):
+ * kernel 1 writes xhat (I/O dtype) and the statistics to HBM, kernel 2 reads xhat back and
+ * applies the per-sample modulation.  xhat_tmp: [B*S, D] scratch in the I/O dtype.
+ *
+ * lnmod_copy: plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16), the
+ * practical bandwidth ceiling the kernels are compared with.
+ */
+int lnmod_unfused_forward(const void* x, const void* shift, const void* scale,
+                          int64_t B, int64_t S, int64_t D, float eps, void* stream,
+                          void* xhat_tmp, void* y, float* mean, float* rstd, int dtype);
+int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LNMOD_H */

@@ -1,0 +1,181 @@
+// lnmod_api.cpp -- the C ABI declared in include/lnmod.h: argument validation (before any HIP
+// call, so that it can be exercised on a host without a GPU) and hand-over to the launchers.
+#include "lnmod.h"
+
+#include <cmath>
+
+#include "lnmod_launch.hpp"
+
+namespace {
+
+using lnmod::Problem;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int64_t nseg, int64_t S_or_T, int64_t D, float eps, int dtype, int64_t total) {
+    if (nseg < 0 || S_or_T < 0 || D < 0) return LNMOD_EINVAL;
+    if (!(std::isfinite(eps) && eps > 0.0f)) return LNMOD_EINVAL;
+    if (dtype != LNMOD_BF16 && dtype != LNMOD_F32) return LNMOD_EINVAL;
+    if (total < 0 || total >= (int64_t(1) << 31)) return LNMOD_EINVAL;
+    const int64_t vec = dtype == LNMOD_BF16 ? 8 : 4;
+    if (D < 8 || D > lnmod::kMaxD || D % vec != 0) return LNMOD_EUNSUPPORTED;
+    return LNMOD_OK;
+}
+
+// total tokens of a fixed-length batch, or -1 on overflow
+int64_t total_tokens(int64_t B, int64_t S) {
+    if (B < 0 || S < 0) return -1;
+    if (B == 0 || S == 0) return 0;
+    if (B > (int64_t(1) << 31) / S) return -1;
+    return B * S;
+}
+
+size_t workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
+    // grid of the widest split over both dtypes, plus one extra slot per segment
+    int64_t blocks = lnmod::bwd_num_blocks(T, D, LNMOD_BF16);
+    const int64_t b2 = lnmod::bwd_num_blocks(T, D, LNMOD_F32);
+    if (b2 > blocks) blocks = b2;
+    return static_cast<size_t>(blocks + nseg) * 2u * static_cast<size_t>(D) * sizeof(float);
+}
+
+int forward_impl(const void* x, const void* shift, const void* scale, const int32_t* cu,
+                 bool varlen, int64_t nseg, int64_t S, int64_t T, int64_t D, float eps,
+                 void* stream, void* y, float* mean, float* rstd, int dtype, int mod) {
+    if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
+    const int st = check_shape(nseg, varlen ? T : S, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    if (T == 0) return LNMOD_OK;
+    if (nseg == 0) return LNMOD_EINVAL;           // tokens that belong to no segment
+    if (!x || !shift || !scale || !y || !mean || !rstd || (varlen && !cu)) return LNMOD_EINVAL;
+    if (!aligned16(x) || !aligned16(shift) || !aligned16(scale) || !aligned16(y)) return LNMOD_EALIGN;
+    const Problem p{dtype, varlen ? cu : nullptr, nseg, S, T, D, eps};
+    const hipStream_t hs = static_cast<hipStream_t>(stream);
+    const hipError_t e = (mod == LNMOD_PER_TOKEN)
+                             ? lnmod::launch_fwd_tok(p, x, shift, scale, y, mean, rstd, hs)
+                             : lnmod::launch_fwd_seg(p, x, shift, scale, y, mean, rstd, hs);
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int backward_impl(const void* dy, const void* x, const void* scale, const int32_t* cu, bool varlen,
+                  int64_t nseg, int64_t S, int64_t T, int64_t D, float eps, void* stream,
+                  const float* mean, const float* rstd, void* dx, void* dshift, void* dscale,
+                  void* workspace, size_t workspace_size, int dtype, int mod) {
+    if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
+    const int st = check_shape(nseg, varlen ? T : S, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    const hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (T == 0) {
+        if (mod == LNMOD_PER_SAMPLE && nseg > 0) {      // empty sums are zeros
+            if (!dshift || !dscale) return LNMOD_EINVAL;
+            if (!aligned16(dshift) || !aligned16(dscale)) return LNMOD_EALIGN;
+            hipError_t e = lnmod::launch_zero_f32(static_cast<float*>(dshift), nseg * D, hs);
+            if (e == hipSuccess) e = lnmod::launch_zero_f32(static_cast<float*>(dscale), nseg * D, hs);
+            return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+        }
+        return LNMOD_OK;
+    }
+    if (nseg == 0) return LNMOD_EINVAL;
+    if (!dy || !x || !scale || !mean || !rstd || !dx || !dshift || !dscale || (varlen && !cu))
+        return LNMOD_EINVAL;
+    if (!aligned16(dy) || !aligned16(x) || !aligned16(scale) || !aligned16(dx) ||
+        !aligned16(dshift) || !aligned16(dscale))
+        return LNMOD_EALIGN;
+    const Problem p{dtype, varlen ? cu : nullptr, nseg, S, T, D, eps};
+    hipError_t e;
+    if (mod == LNMOD_PER_TOKEN) {
+        e = lnmod::launch_bwd_tok(p, dy, x, scale, mean, rstd, dx, dshift, dscale, hs);
+    } else {
+        if (!workspace || workspace_size < workspace_bytes(nseg, T, D)) return LNMOD_EWORKSPACE;
+        if (!aligned16(workspace)) return LNMOD_EALIGN;
+        e = lnmod::launch_bwd_seg(p, dy, x, scale, mean, rstd, dx, static_cast<float*>(dshift),
+                                  static_cast<float*>(dscale), static_cast<float*>(workspace), hs);
+    }
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lnmod_forward(const void* x, const void* shift, const void* scale, int64_t B, int64_t S,
+                  int64_t D, float eps, void* stream, void* y, float* mean, float* rstd,
+                  int dtype, int mod) {
+    const int64_t T = total_tokens(B, S);
+    if (T < 0) return LNMOD_EINVAL;
+    return forward_impl(x, shift, scale, nullptr, false, B, S, T, D, eps, stream, y, mean, rstd,
+                        dtype, mod);
+}
+
+int lnmod_backward(const void* dy, const void* x, const void* shift, const void* scale, int64_t B,
+                   int64_t S, int64_t D, float eps, void* stream, const float* mean,
+                   const float* rstd, void* dx, void* dshift, void* dscale, void* workspace,
+                   size_t workspace_size, int dtype, int mod) {
+    (void)shift;
+    const int64_t T = total_tokens(B, S);
+    if (T < 0) return LNMOD_EINVAL;
+    return backward_impl(dy, x, scale, nullptr, false, B, S, T, D, eps, stream, mean, rstd, dx,
+                         dshift, dscale, workspace, workspace_size, dtype, mod);
+}
+
+int lnmod_forward_varlen(const void* x, const void* shift, const void* scale,
+                         const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D, float eps,
+                         void* stream, void* y, float* mean, float* rstd, int dtype) {
+    return forward_impl(x, shift, scale, cu_seqlens, true, nseg, 0, T, D, eps, stream, y, mean,
+                        rstd, dtype, LNMOD_PER_SAMPLE);
+}
+
+int lnmod_backward_varlen(const void* dy, const void* x, const void* shift, const void* scale,
+                          const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D, float eps,
+                          void* stream, const float* mean, const float* rstd, void* dx,
+                          void* dshift, void* dscale, void* workspace, size_t workspace_size,
+                          int dtype) {
+    (void)shift;
+    return backward_impl(dy, x, scale, cu_seqlens, true, nseg, 0, T, D, eps, stream, mean, rstd,
+                         dx, dshift, dscale, workspace, workspace_size, dtype, LNMOD_PER_SAMPLE);
+}
+
+size_t lnmod_backward_workspace_bytes(int64_t B_or_nseg, int64_t total, int64_t D, int mod) {
+    if (mod != LNMOD_PER_SAMPLE) return 0;
+    if (B_or_nseg < 0 || total < 0 || total >= (int64_t(1) << 31)) return 0;
+    if (D < 8 || D > lnmod::kMaxD || D % 4 != 0) return 0;
+    return workspace_bytes(B_or_nseg, total, D);
+}
+
+const char* lnmod_status_string(int status) {
+    switch (status) {
+        case LNMOD_OK: return "ok";
+        case LNMOD_EINVAL: return "invalid argument";
+        case LNMOD_EUNSUPPORTED: return "unsupported hidden size";
+        case LNMOD_EALIGN: return "pointer not 16-byte aligned";
+        case LNMOD_EWORKSPACE: return "workspace missing or too small";
+        case LNMOD_ELAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int lnmod_unfused_forward(const void* x, const void* shift, const void* scale, int64_t B, int64_t S,
+                          int64_t D, float eps, void* stream, void* xhat_tmp, void* y, float* mean,
+                          float* rstd, int dtype) {
+    const int64_t T = total_tokens(B, S);
+    if (T < 0) return LNMOD_EINVAL;
+    const int st = check_shape(B, S, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    if (T == 0) return LNMOD_OK;
+    if (!x || !shift || !scale || !xhat_tmp || !y || !mean || !rstd) return LNMOD_EINVAL;
+    if (!aligned16(x) || !aligned16(shift) || !aligned16(scale) || !aligned16(xhat_tmp) || !aligned16(y))
+        return LNMOD_EALIGN;
+    const Problem p{dtype, nullptr, B, S, T, D, eps};
+    const hipError_t e = lnmod::launch_unfused(p, x, shift, scale, xhat_tmp, y, mean, rstd,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (bytes == 0) return LNMOD_OK;
+    if (!src || !dst || bytes % 16 != 0) return LNMOD_EINVAL;
+    if (!aligned16(src) || !aligned16(dst)) return LNMOD_EALIGN;
+    const hipError_t e = lnmod::launch_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+}  // extern "C"

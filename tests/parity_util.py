@@ -1,0 +1,92 @@
+"""Comparison helpers for the GPU-vs-oracle parity tests.
+
+Tolerances (stated by the workload definition: bf16 I/O max abs 2e-2 and relative L2 4e-3;
+fp32 I/O 1e-5 relative; mean/rstd 1e-5 relative), read as follows:
+
+  bf16 tensors   rel-L2 <= 4e-3 and, element by element, |err| <= 2e-2 + 2^-8 |ref|: the plain
+                 2e-2 bound cannot hold where |ref| >= 8, because rounding the exact result to
+                 bf16 already moves it by up to 2^-9 |ref| there.  In addition every GPU value
+                 must lie within one bf16 ulp of the correctly rounded reference.
+  fp32 tensors   rel-L2 <= 1e-5 and max|err| <= 1e-5 max|ref| (also used for the float32
+                 dshift/dscale sums of the bf16 workloads).
+  rstd           element-wise relative error <= 1e-5.
+  mean           |err| <= 1e-5 max(|mean_ref|, std_ref): a pure relative bound is ill-posed for
+                 rows whose mean happens to be near zero.
+"""
+import numpy as np
+import torch
+
+
+def to_device(a, dtype, device="cuda"):
+    """float32 host array (already exact in `dtype`) -> device tensor of that dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == "bf16":
+        return t.to(torch.bfloat16).to(device)
+    return t.to(device)
+
+
+def to_host64(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_l2(got, ref):
+    den = float(np.linalg.norm(ref.ravel()))
+    num = float(np.linalg.norm((got - ref).ravel()))
+    return num / den if den > 0 else num
+
+
+def bf16_round(a64):
+    """Correctly rounded (nearest even) bf16 value of float64 data, as float64.  Rounds from
+    float64 in one step (via the float32 value and a sticky correction is not needed: torch
+    rounds double -> bfloat16 directly)."""
+    return torch.from_numpy(np.ascontiguousarray(a64)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def bf16_ulp(a64):
+    a = np.abs(a64)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+def check_io_tensor(name, got_t, ref64, dtype):
+    got = to_host64(got_t).reshape(ref64.shape)
+    assert np.all(np.isfinite(got)), name + ": non-finite values"
+    err = np.abs(got - ref64)
+    if dtype == "bf16":
+        r = rel_l2(got, ref64)
+        assert r <= 4e-3, "%s: rel-L2 %.3e > 4e-3" % (name, r)
+        bound = 2e-2 + 2.0 ** -8 * np.abs(ref64)
+        bad = err > bound
+        assert not bad.any(), "%s: %d elements beyond 2e-2 + 2^-8|ref| (worst %.3e at |ref| %.3e)" % (
+            name, int(bad.sum()), float(err.max()), float(np.abs(ref64).ravel()[err.argmax()]))
+        rounded = bf16_round(ref64)
+        ulp = bf16_ulp(rounded)
+        off = np.abs(got - rounded) > ulp * 1.0001
+        assert not off.any(), "%s: %d elements more than one bf16 ulp from the rounded reference" % (
+            name, int(off.sum()))
+    else:
+        check_f32_tensor(name, got, ref64)
+    return float(err.max())
+
+
+def check_f32_tensor(name, got, ref64, rel=1e-5):
+    if isinstance(got, torch.Tensor):
+        got = to_host64(got)
+    got = got.reshape(ref64.shape)
+    assert np.all(np.isfinite(got)), name + ": non-finite values"
+    r = rel_l2(got, ref64)
+    assert r <= rel, "%s: rel-L2 %.3e > %.1e" % (name, r, rel)
+    scale = float(np.abs(ref64).max()) if ref64.size else 0.0
+    worst = float(np.abs(got - ref64).max()) if ref64.size else 0.0
+    assert worst <= rel * scale + 1e-30, "%s: max err %.3e > %.1e * %.3e" % (name, worst, rel, scale)
+
+
+def check_stats(mean_t, rstd_t, mean64, rstd64):
+    mean = to_host64(mean_t).reshape(mean64.shape)
+    rstd = to_host64(rstd_t).reshape(rstd64.shape)
+    rel = np.abs(rstd - rstd64) / rstd64
+    assert rel.max() <= 1e-5, "rstd: relative error %.3e > 1e-5" % rel.max()
+    std = 1.0 / rstd64
+    bound = 1e-5 * np.maximum(np.abs(mean64), std)
+    assert np.all(np.abs(mean - mean64) <= bound), "mean: error %.3e beyond 1e-5*max(|mean|, std)" % (
+        np.abs(mean - mean64).max())

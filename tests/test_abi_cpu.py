@@ -1,0 +1,143 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lnmod.h")
+
+from paper_2605_17923_amd import lnmod  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lnmod.LIBRARY):
+        from paper_2605_17923_amd.build import build_library
+        build_library()
+    return lnmod.library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lnmod_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(lnmod.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_mirrors_every_entry_point():
+    for n in declared_functions():
+        assert callable(getattr(lnmod, n)), n
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(6):
+        s = lnmod.lnmod_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 6
+    assert lnmod.lnmod_status_string(99) == "unknown status"
+
+
+A = 0x1000          # a 16-byte aligned fake address; validation never dereferences it
+
+
+def fwd(x=A, shift=A, scale=A, B=2, S=4, D=64, eps=1e-6, y=A, mean=A, rstd=A, dtype=0, mod=0):
+    return lnmod.lnmod_forward(x, shift, scale, B, S, D, eps, None, y, mean, rstd, dtype, mod)
+
+
+def bwd(dy=A, x=A, scale=A, B=2, S=4, D=64, eps=1e-6, mean=A, rstd=A, dx=A, dshift=A, dscale=A,
+        ws=A, ws_bytes=1 << 40, dtype=0, mod=0):
+    return lnmod.lnmod_backward(dy, x, None, scale, B, S, D, eps, None, mean, rstd, dx, dshift,
+                                dscale, ws, ws_bytes, dtype, mod)
+
+
+def test_forward_rejects_bad_arguments(lib):
+    assert fwd(x=None) == lnmod.LNMOD_EINVAL
+    assert fwd(shift=None) == lnmod.LNMOD_EINVAL
+    assert fwd(mean=None) == lnmod.LNMOD_EINVAL
+    assert fwd(B=-1) == lnmod.LNMOD_EINVAL
+    assert fwd(S=-1) == lnmod.LNMOD_EINVAL
+    assert fwd(B=1 << 20, S=1 << 20) == lnmod.LNMOD_EINVAL          # 2^40 tokens
+    assert fwd(eps=0.0) == lnmod.LNMOD_EINVAL
+    assert fwd(eps=-1e-6) == lnmod.LNMOD_EINVAL
+    assert fwd(eps=float("nan")) == lnmod.LNMOD_EINVAL
+    assert fwd(eps=float("inf")) == lnmod.LNMOD_EINVAL
+    assert fwd(dtype=2) == lnmod.LNMOD_EINVAL
+    assert fwd(mod=2) == lnmod.LNMOD_EINVAL
+    assert fwd(D=0) == lnmod.LNMOD_EUNSUPPORTED
+    assert fwd(D=60) == lnmod.LNMOD_EUNSUPPORTED                    # bf16 needs a multiple of 8
+    assert fwd(D=62, dtype=1) == lnmod.LNMOD_EUNSUPPORTED           # fp32 needs a multiple of 4
+    assert fwd(D=8200) == lnmod.LNMOD_EUNSUPPORTED
+    assert fwd(x=A + 8) == lnmod.LNMOD_EALIGN
+    assert fwd(y=A + 2) == lnmod.LNMOD_EALIGN
+    # nothing to do: fine, and nothing is enqueued
+    assert fwd(B=0) == lnmod.LNMOD_OK
+    assert fwd(S=0) == lnmod.LNMOD_OK
+    assert fwd(S=0, x=None, y=None) == lnmod.LNMOD_OK
+
+
+def test_backward_rejects_bad_arguments(lib):
+    assert bwd(dy=None) == lnmod.LNMOD_EINVAL
+    assert bwd(dscale=None) == lnmod.LNMOD_EINVAL
+    assert bwd(rstd=None) == lnmod.LNMOD_EINVAL
+    assert bwd(D=12) == lnmod.LNMOD_EUNSUPPORTED
+    assert bwd(dx=A + 4) == lnmod.LNMOD_EALIGN
+    assert bwd(ws=None) == lnmod.LNMOD_EWORKSPACE
+    need = lnmod.lnmod_backward_workspace_bytes(2, 8, 64, 0)
+    assert need > 0
+    assert bwd(ws_bytes=need - 1) == lnmod.LNMOD_EWORKSPACE
+    assert bwd(ws=A + 4, ws_bytes=need) == lnmod.LNMOD_EALIGN
+    assert bwd(mod=3) == lnmod.LNMOD_EINVAL
+    assert bwd(B=0) == lnmod.LNMOD_OK
+    assert bwd(S=0, mod=1) == lnmod.LNMOD_OK
+
+
+def test_varlen_rejects_bad_arguments(lib):
+    f = lnmod.lnmod_forward_varlen
+    assert f(A, A, A, None, 3, 10, 64, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
+    assert f(A, A, A, A, -1, 10, 64, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
+    assert f(A, A, A, A, 0, 10, 64, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_EINVAL   # tokens, no segment
+    assert f(A, A, A, A, 3, 1 << 31, 64, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
+    assert f(A, A, A, A, 3, 10, 65, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_EUNSUPPORTED
+    assert f(A, A, A, A, 3, 0, 64, 1e-6, None, A, A, A, 0) == lnmod.LNMOD_OK
+    b = lnmod.lnmod_backward_varlen
+    assert b(A, A, None, A, A, 3, 10, 64, 1e-6, None, A, A, A, A, A, None, 0, 0) == lnmod.LNMOD_EWORKSPACE
+    assert b(A, A, None, A, None, 3, 10, 64, 1e-6, None, A, A, A, A, A, A, 1 << 40, 0) == lnmod.LNMOD_EINVAL
+
+
+def test_workspace_query(lib):
+    q = lnmod.lnmod_backward_workspace_bytes
+    assert q(1, 75600, 5120, lnmod.LNMOD_PER_TOKEN) == 0
+    assert q(-1, 10, 64, 0) == 0 and q(1, -1, 64, 0) == 0 and q(1, 10, 66, 0) == 0
+    n = q(1, 75600, 5120, 0)
+    assert n % (2 * 5120 * 4) == 0 and 0 < n <= (2048 + 1) * 2 * 5120 * 4
+    # more segments need more slots; the size is monotone in the token count up to the grid cap
+    assert q(24, 75600, 5120, 0) == n + 23 * 2 * 5120 * 4
+    assert q(1, 10, 5120, 0) <= n
+
+
+def test_copy_and_unfused_reject_bad_arguments(lib):
+    assert lnmod.lnmod_copy(None, A, 64, None) == lnmod.LNMOD_EINVAL
+    assert lnmod.lnmod_copy(A, A, 60, None) == lnmod.LNMOD_EINVAL
+    assert lnmod.lnmod_copy(A + 4, A, 64, None) == lnmod.LNMOD_EALIGN
+    assert lnmod.lnmod_copy(A, A, 0, None) == lnmod.LNMOD_OK
+    u = lnmod.lnmod_unfused_forward
+    assert u(A, A, A, 2, 4, 64, 1e-6, None, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
+    assert u(A, A, A, 2, 4, 63, 1e-6, None, A, A, A, A, 0) == lnmod.LNMOD_EUNSUPPORTED
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(lnmod, "_lib", None)
+    monkeypatch.setattr(lnmod, "LIBRARY", os.path.join(tmp_path, "nope.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        lnmod.lnmod_forward(A, A, A, 1, 1, 64, 1e-6, None, A, A, A, 0, 0)

@@ -1,0 +1,258 @@
+"""GPU parity: the gfx950 kernels, called through the C ABI, against the float64 CPU oracle on
+the same seeded inputs.  Small shapes (several tiles, ragged tails, odd hidden sizes, empty
+segments) are compared element by element; the full-size workloads are compared in the launch
+configuration the benchmark times, on sampled token rows plus the complete dshift/dscale sums."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_17923_amd import lnmod, synth
+from parity_util import check_f32_tensor, check_io_tensor, check_stats, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lnmod.library()                      # fails loudly if the HIP library is not built
+    yield
+    torch.cuda.synchronize()
+
+
+def run_case(inp, check_bwd=True, sample_rows=None, label=""):
+    """Forward (+ backward) of one workload through the C ABI, checked against the oracle."""
+    w = inp.workload
+    dt = w.dtype
+    T, D, B = inp.T, inp.D, inp.B
+    per_token = w.mod == synth.PER_TOKEN
+    print("case", label or w.name, "dtype", dt, "T", T, "D", D, "B", B, "varlen", w.varlen, flush=True)
+    x = to_device(inp.x, dt)
+    shift = to_device(inp.shift, dt)
+    scale = to_device(inp.scale, dt)
+    cu64 = inp.cu_seqlens.astype(np.int64)
+    cu_dev = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+    if w.varlen:
+        y, mean, rstd = lnmod.forward_varlen(x, shift, scale, cu_dev, w.eps)
+    else:
+        S = inp.S
+        y, mean, rstd = lnmod.forward(x.view(B, S, D),
+                                      shift.view(B, S, D) if per_token else shift,
+                                      scale.view(B, S, D) if per_token else scale, w.eps)
+    torch.cuda.synchronize()
+    omod = oracle.PER_TOKEN if per_token else oracle.PER_SEGMENT
+
+    if sample_rows is None:
+        rows = np.arange(T)
+    else:
+        rows = np.asarray(sample_rows, dtype=np.int64)
+    seg_of = np.searchsorted(cu64, rows, side="right") - 1
+
+    def oracle_rows_forward():
+        # rows are independent in the forward: evaluate the sampled rows one segment at a time
+        ys = np.empty((rows.size, D))
+        ms = np.empty(rows.size)
+        rs = np.empty(rows.size)
+        if per_token:
+            ys, ms, rs = oracle.forward(inp.x[rows], inp.shift[rows], inp.scale[rows], w.eps,
+                                        B=1, S=rows.size, mod=oracle.PER_TOKEN)
+            return ys, ms, rs
+        for m in np.unique(seg_of):
+            sel = np.nonzero(seg_of == m)[0]
+            a, b, c = oracle.forward(inp.x[rows[sel]], inp.shift[m:m + 1], inp.scale[m:m + 1], w.eps,
+                                     B=1, S=sel.size)
+            ys[sel], ms[sel], rs[sel] = a, b, c
+        return ys, ms, rs
+
+    if sample_rows is None:
+        y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, w.eps, cu=cu64, mod=omod)
+    else:
+        y64, mean64, rstd64 = oracle_rows_forward()
+    rows_t = torch.from_numpy(rows).cuda()
+    check_io_tensor("y", y.reshape(T, D)[rows_t], y64, dt)
+    check_stats(mean.reshape(T)[rows_t], rstd.reshape(T)[rows_t], mean64, rstd64)
+
+    if not (check_bwd and inp.dy is not None):
+        return
+    dy = to_device(inp.dy, dt)
+    if w.varlen:
+        dx, dsh, dsc = lnmod.backward_varlen(dy, x, scale, cu_dev, mean, rstd, w.eps)
+    else:
+        S = inp.S
+        dx, dsh, dsc = lnmod.backward(dy.view(B, S, D), x.view(B, S, D),
+                                      scale.view(B, S, D) if per_token else scale,
+                                      mean.reshape(B, S), rstd.reshape(B, S), w.eps)
+    torch.cuda.synchronize()
+    dx64, dsh64, dsc64 = oracle.backward(inp.dy, inp.x, inp.scale, w.eps, cu=cu64, mod=omod)
+    check_io_tensor("dx", dx.reshape(T, D)[rows_t], dx64[rows], dt)
+    if per_token:
+        check_io_tensor("dshift", dsh.reshape(T, D)[rows_t], dsh64[rows], dt)
+        check_io_tensor("dscale", dsc.reshape(T, D)[rows_t], dsc64[rows], dt)
+    else:
+        check_f32_tensor("dshift", dsh, dsh64)
+        check_f32_tensor("dscale", dsc, dsc64)
+
+
+# ---- configs[0] as is, and reduced versions of configs[1..4] ------------------------------------
+def test_config0_tiny_fp32():
+    run_case(synth.make_inputs(0))
+
+
+def test_config1_reduced():
+    run_case(synth.make_inputs(1, S=2311, with_dy=True))
+
+
+def test_config2_reduced_outliers():
+    run_case(synth.make_inputs(2, S=2053))
+
+
+def test_config3_reduced_per_token():
+    run_case(synth.make_inputs(3, S=517))
+
+
+def test_config4_reduced_varlen():
+    lengths = (37, 0, 1560, 5, 819, 1, 0, 0, 300, 64, 2, 777, 0)
+    run_case(synth.make_inputs(4, lengths=lengths))
+
+
+def test_varlen_leading_and_trailing_empty_segments():
+    run_case(synth.make_inputs(4, lengths=(0, 0, 129, 0), D=1536))
+    run_case(synth.make_inputs(4, lengths=(1,), D=1536))
+    run_case(synth.make_inputs(4, lengths=(3000, 1, 1, 1, 2999), D=512))
+
+
+@pytest.mark.parametrize("B,S", [(5, 77), (3, 1), (1, 1), (64, 9), (2, 2500)])
+def test_multi_sample_ranges_cross_blocks(B, S):
+    run_case(synth.make_inputs(2, B=B, S=S), label="multi-sample B=%d S=%d" % (B, S))
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 8), ("bf16", 520), ("bf16", 1024), ("bf16", 1544),
+                                     ("bf16", 3072), ("bf16", 4096), ("bf16", 6144), ("bf16", 7000),
+                                     ("bf16", 8192),
+                                     ("f32", 8), ("f32", 100), ("f32", 260), ("f32", 1024),
+                                     ("f32", 3076), ("f32", 5120), ("f32", 8192)])
+def test_hidden_sizes(dtype, D):
+    run_case(synth.make_inputs(0, B=3, S=45, D=D, dtype=dtype), label="D=%d %s" % (D, dtype))
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 1536), ("bf16", 520), ("bf16", 8192), ("f32", 1536),
+                                     ("f32", 100), ("f32", 6144)])
+def test_hidden_sizes_per_token(dtype, D):
+    run_case(synth.make_inputs(3, B=2, S=67, D=D, dtype=dtype), label="per-token D=%d %s" % (D, dtype))
+
+
+def test_constant_rows_and_large_offsets():
+    # constant row: var = 0, rstd = 1/sqrt(eps), y = shift; a row far from zero (mean 30 sigma):
+    # the centred two-pass variance keeps its accuracy where E[x^2]-mean^2 would lose 3 digits
+    inp = synth.make_inputs(0, B=1, S=8, D=1536, dtype="f32")
+    inp.x[0, :] = 3.25
+    inp.x[1, :] += 30.0
+    run_case(inp, label="degenerate rows")
+
+
+# ---- full-size workloads in the benchmark's launch configuration --------------------------------
+def _sample_rows(T, cu, n=1500, seed=7):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, T, n).tolist())
+    rows.update([0, 1, 2, 3, T - 1, T - 2, T - 3, T - 4])
+    for c in np.asarray(cu, dtype=np.int64):
+        for d in (-2, -1, 0, 1):
+            if 0 <= c + d < T:
+                rows.add(int(c + d))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def test_config1_full_size():
+    inp = synth.make_inputs(1)
+    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+def test_config2_full_size():
+    inp = synth.make_inputs(2)
+    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+def test_config3_full_size():
+    inp = synth.make_inputs(3)
+    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+def test_config4_full_size():
+    inp = synth.make_inputs(4)
+    assert 140_000 <= inp.T <= 160_000 and inp.B == 24
+    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+# ---- behaviour of the boundary ------------------------------------------------------------------
+def test_backward_is_bitwise_reproducible_and_uses_saved_stats():
+    inp = synth.make_inputs(2, S=3001)
+    x = to_device(inp.x, "bf16").view(1, -1, inp.D)
+    dy = to_device(inp.dy, "bf16").view(1, -1, inp.D)
+    scale = to_device(inp.scale, "bf16")
+    shift = to_device(inp.shift, "bf16")
+    y1, mean, rstd = lnmod.forward(x, shift, scale)
+    y2, _, _ = lnmod.forward(x, shift, scale)
+    a = lnmod.backward(dy, x, scale, mean, rstd)
+    b = lnmod.backward(dy, x, scale, mean, rstd)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    for u, v in zip(a, b):
+        assert torch.equal(u, v)
+    # the backward reads the statistics the forward saved: other statistics, other dx
+    c = lnmod.backward(dy, x, scale, mean + 0.5, rstd * 2.0)
+    torch.cuda.synchronize()
+    assert not torch.equal(a[0], c[0])
+    assert torch.equal(a[1], c[1])                  # dshift does not depend on them
+
+
+def test_runs_on_the_given_stream_and_overwrites_outputs():
+    inp = synth.make_inputs(0)
+    x = to_device(inp.x, "f32").view(inp.B, inp.S, inp.D)
+    shift, scale = to_device(inp.shift, "f32"), to_device(inp.scale, "f32")
+    y_ref, mean_ref, rstd_ref = lnmod.forward(x, shift, scale)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    y = torch.full_like(x, float("nan"))
+    mean = torch.full((inp.T,), float("nan"), device="cuda")
+    rstd = torch.full((inp.T,), float("nan"), device="cuda")
+    torch.cuda.synchronize()
+    rc = lnmod.lnmod_forward(x, shift, scale, inp.B, inp.S, inp.D, 1e-6, st.cuda_stream, y, mean, rstd,
+                             lnmod.LNMOD_F32, lnmod.LNMOD_PER_SAMPLE)
+    assert rc == lnmod.LNMOD_OK
+    st.synchronize()
+    assert torch.equal(y, y_ref) and torch.equal(mean.view_as(mean_ref), mean_ref)
+    assert torch.equal(rstd.view_as(rstd_ref), rstd_ref)
+
+
+def test_empty_batch_zero_fills_reduced_gradients():
+    D = 256
+    dsh = torch.full((3, D), 7.0, device="cuda")
+    dsc = torch.full((3, D), 7.0, device="cuda")
+    rc = lnmod.lnmod_backward(None, None, None, None, 3, 0, D, 1e-6, torch.cuda.current_stream().cuda_stream,
+                              None, None, None, dsh, dsc, None, 0, lnmod.LNMOD_BF16, lnmod.LNMOD_PER_SAMPLE)
+    torch.cuda.synchronize()
+    assert rc == lnmod.LNMOD_OK
+    assert float(dsh.abs().max()) == 0.0 and float(dsc.abs().max()) == 0.0
+
+
+def test_unfused_comparator_and_copy_match():
+    inp = synth.make_inputs(1, S=1000)
+    x = to_device(inp.x, "bf16")
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    tmp, y = torch.empty_like(x), torch.empty_like(x)
+    mean = torch.empty(inp.T, device="cuda")
+    rstd = torch.empty(inp.T, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    assert lnmod.lnmod_unfused_forward(x, shift, scale, 1, inp.T, inp.D, 1e-6, s, tmp, y, mean, rstd,
+                                       lnmod.LNMOD_BF16) == lnmod.LNMOD_OK
+    torch.cuda.synchronize()
+    y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, B=1, S=inp.T)
+    # xhat is rounded to bf16 before the modulation, so only the coarse bounds apply here
+    got = y.double().cpu().numpy()
+    assert np.abs(got - y64).max() <= 2e-2 + 2.0 ** -7 * np.abs(y64).max()
+    check_stats(mean, rstd, mean64, rstd64)
+    dst = torch.zeros_like(x)
+    assert lnmod.lnmod_copy(x, dst, x.numel() * 2, s) == lnmod.LNMOD_OK
+    torch.cuda.synchronize()
+    assert torch.equal(dst, x)
