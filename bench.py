@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LayerNorm-Modulate hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the Wan-14B-shaped workload
+(bf16, B=1, S=75600 tokens, D=5120): lnmod_forward (y, mean, rstd) followed by lnmod_backward
+(dx, dshift, dscale; the fused dx+partials kernel and its fixed-order second pass).  Inputs are
+synthetic, generated on the device from a seeded generator with the workload's distributions,
+and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is algorithmic HBM bytes of a step / wall time of a step
+(GB/s); `roofline` describes the dominant launch (the backward) and `roofline_fwd` the forward
+kernel, both from HIP events recorded on the launch stream inside the timed region;
+`cpu_baseline` is the float64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
+# same counters' reading for lnmod_copy of known size; see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {"forward": None, "backward": None}
+
+
+def algorithmic_bytes(T, D, elem):
+    """Bytes the method itself must move per launch.  Forward: x in, y out, mean+rstd out.
+    Backward: dy, x in, dx out, mean+rstd in (the per-block partial sums and the [B,2,D] result
+    are excluded: they are this implementation's choice, about 1 % extra)."""
+    fwd = T * (2 * D * elem + 8)
+    bwd = T * (3 * D * elem + 8)
+    return fwd, bwd
+
+
+def make_device_inputs(T, D, seed, device):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    x = torch.randn(T, D, generator=g, device=device) * 2.0 + 0.5
+    mask = torch.rand(T, D, generator=g, device=device) < 1e-3
+    x = torch.where(mask, x * 50.0, x).to(torch.bfloat16)
+    del mask
+    dy = torch.randn(T, D, generator=g, device=device).to(torch.bfloat16)
+    shift = (0.1 * torch.randn(1, D, generator=g, device=device)).to(torch.bfloat16)
+    scale = (0.1 * torch.randn(1, D, generator=g, device=device)).to(torch.bfloat16)
+    return x, dy, shift, scale
+
+
+def cpu_baseline(D, sample_tokens, repeats=3):
+    """The oracle as it stands, forward + backward on `sample_tokens` tokens of the workload
+    (host-generated from the workload's recipe), median of `repeats` runs."""
+    import oracle
+    from paper_2605_17923_amd import synth
+    inp = synth.make_inputs(2, S=sample_tokens)
+    oracle.forward(inp.x[:64], inp.shift, inp.scale, 1e-6, B=1, S=64)      # load + warm the library
+    times = []
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        oracle.forward(inp.x, inp.shift, inp.scale, 1e-6, B=1, S=sample_tokens)
+        oracle.backward(inp.dy, inp.x, inp.scale, 1e-6, B=1, S=sample_tokens)
+        times.append(time.perf_counter() - t0)
+    dt = sorted(times)[len(times) // 2]
+    fwd_b, bwd_b = algorithmic_bytes(sample_tokens, D, 2)
+    return {"value": round((fwd_b + bwd_b) / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "tokens_per_s": round(sample_tokens / dt), "seconds": round(dt, 3),
+            "sample": "%d of the workload's 75600 tokens (fwd+bwd, float64 C, OpenMP over rows), "
+                      "median of %d runs" % (sample_tokens, repeats)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=75600)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the copy ceiling, the unfused comparison and the D=1536 forward")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the operator has no cross-GPU step); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_17923_amd import lnmod
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    lnmod.library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B, S, D = 1, 75600, 5120
+    T = B * S
+    x, dy, shift, scale = make_device_inputs(T, D, 1003, dev)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    mean = torch.empty(T, dtype=torch.float32, device=dev)
+    rstd = torch.empty(T, dtype=torch.float32, device=dev)
+    dshift = torch.empty(B, D, dtype=torch.float32, device=dev)
+    dscale = torch.empty(B, D, dtype=torch.float32, device=dev)
+    ws = lnmod.workspace(B, T, D, dev)
+    stream = torch.cuda.current_stream()
+    st = stream.cuda_stream
+    BF16, PER_SAMPLE = lnmod.LNMOD_BF16, lnmod.LNMOD_PER_SAMPLE
+
+    def fwd():
+        rc = lnmod.lnmod_forward(x, shift, scale, B, S, D, 1e-6, st, y, mean, rstd, BF16, PER_SAMPLE)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    def bwd():
+        rc = lnmod.lnmod_backward(dy, x, None, scale, B, S, D, 1e-6, st, mean, rstd, dx, dshift,
+                                  dscale, ws, ws.numel(), BF16, PER_SAMPLE)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    for _ in range(args.warmup):
+        fwd()
+        bwd()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        ev[k][0].record(stream)
+        fwd()
+        ev[k][1].record(stream)
+        bwd()
+        ev[k][2].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
+    ms_per_step = wall * 1e3 / K
+    fwd_b, bwd_b = algorithmic_bytes(T, D, 2)
+    value = (fwd_b + bwd_b) / (ms_per_step * 1e-3) / 1e9
+
+    def roof(nbytes, ms, kernel, traffic):
+        a = nbytes / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": kernel, "achieved": round(a, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(ms * 1e3, 2), "algorithmic_bytes": nbytes,
+                "tokens_per_s": round(T / (ms * 1e-3))}
+
+    out = {
+        "metric": "achieved HBM GB/s (% of MI355X peak) + tokens/s, LN-Modulate fwd/bwd",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[2] Wan-14B-shaped fwd+bwd: bf16 I/O, B=1, S=75600, D=5120, "
+                               "x~N(0.5,2) with 0.1% x50 outliers, per-sample shift/scale, eps=1e-6",
+                   "io_dtype": "bf16", "B": B, "S": S, "D": D},
+        "frac_of_peak": round(value / PEAK_HBM_GBS, 4),
+        "tokens_per_s": round(T / (ms_per_step * 1e-3)),
+        "roofline": roof(bwd_b, bwd_ms, "lnmod_backward = bwd_seg_kernel + bwd_reduce_kernel "
+                                        "(durations summed)", MEASURED_TRAFFIC_BYTES["backward"]),
+        "roofline_fwd": roof(fwd_b, fwd_ms, "fwd_seg_kernel", MEASURED_TRAFFIC_BYTES["forward"]),
+    }
+
+    if not args.no_extras:
+        out["extras"] = extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fwd_ms)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(D, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+def _time_ms(torch, stream, fn, iters=20, warm=3):
+    for _ in range(warm):
+        fn()
+    a = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    a[0].record(stream)
+    for i in range(iters):
+        fn()
+        a[i + 1].record(stream)
+    torch.cuda.synchronize()
+    return sum(a[i].elapsed_time(a[i + 1]) for i in range(iters)) / iters
+
+
+def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
+    """Context figures: a plain copy as the practical bandwidth ceiling, the unfused two-kernel
+    forward (LayerNorm -> xhat in HBM -> modulate) and the Wan-1.3B-shaped forward."""
+    res = {}
+    nbytes = x.numel() * 2
+    ms = _time_ms(torch, stream, lambda: lnmod.lnmod_copy(x, y, nbytes, st))
+    res["copy_ceiling_GBs"] = round(2 * nbytes / (ms * 1e-3) / 1e9, 1)
+    tmp = torch.empty_like(x)
+    ms_u = _time_ms(torch, stream, lambda: lnmod.lnmod_unfused_forward(
+        x, shift, scale, 1, T, D, 1e-6, st, tmp, y, mean, rstd, lnmod.LNMOD_BF16))
+    res["unfused_fwd_us"] = round(ms_u * 1e3, 1)
+    res["fused_fwd_us"] = round(fused_fwd_ms * 1e3, 1)
+    res["fused_vs_unfused_fwd_speedup"] = round(ms_u / fused_fwd_ms, 3)
+    del tmp
+    # configs[1]: bf16 forward, B=1, S=32760, D=1536 (201 MB: fits the 256 MB Infinity Cache, so
+    # three buffer sets are rotated to keep the traffic in HBM)
+    S1, D1 = 32760, 1536
+    g = torch.Generator(device=x.device)
+    g.manual_seed(1002)
+    xs = [torch.randn(S1, D1, generator=g, device=x.device).to(torch.bfloat16) for _ in range(3)]
+    ys = [torch.empty_like(t) for t in xs]
+    sh1 = (0.1 * torch.randn(1, D1, generator=g, device=x.device)).to(torch.bfloat16)
+    sc1 = (0.1 * torch.randn(1, D1, generator=g, device=x.device)).to(torch.bfloat16)
+    m1 = torch.empty(S1, device=x.device)
+    r1 = torch.empty(S1, device=x.device)
+    state = {"i": 0}
+
+    def f1():
+        i = state["i"] = (state["i"] + 1) % 3
+        lnmod.lnmod_forward(xs[i], sh1, sc1, 1, S1, D1, 1e-6, st, ys[i], m1, r1, lnmod.LNMOD_BF16,
+                            lnmod.LNMOD_PER_SAMPLE)
+
+    ms1 = _time_ms(torch, stream, f1, iters=30)
+    b1 = S1 * (4 * D1 + 8)
+    res["config1_fwd"] = {"us": round(ms1 * 1e3, 2), "GBs": round(b1 / (ms1 * 1e-3) / 1e9, 1),
+                          "frac": round(b1 / (ms1 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                          "tokens_per_s": round(S1 / (ms1 * 1e-3))}
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -33,7 +33,8 @@
  *   - The return value is the only error channel (no exceptions, no abort, nothing printed).
  *     Arguments are validated before any HIP call, so a bad call enqueues nothing.
  *       LNMOD_EINVAL        NULL required pointer; negative size; eps not finite or <= 0;
- *                           unknown dtype or mod; token count at or above 2^31
+ *                           unknown dtype or mod; token count at or above 2^31; more than
+ *                           2^24 - 1 samples or segments
  *       LNMOD_EUNSUPPORTED  D outside the supported set
  *       LNMOD_EALIGN        a tensor pointer is not 16-byte aligned
  *       LNMOD_EWORKSPACE    workspace NULL or smaller than lnmod_backward_workspace_bytes()

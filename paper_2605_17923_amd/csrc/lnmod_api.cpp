@@ -13,7 +13,7 @@ using lnmod::Problem;
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_shape(int64_t nseg, int64_t S_or_T, int64_t D, float eps, int dtype, int64_t total) {
-    if (nseg < 0 || S_or_T < 0 || D < 0) return LNMOD_EINVAL;
+    if (nseg < 0 || nseg >= (int64_t(1) << 24) || S_or_T < 0 || D < 0) return LNMOD_EINVAL;
     if (!(std::isfinite(eps) && eps > 0.0f)) return LNMOD_EINVAL;
     if (dtype != LNMOD_BF16 && dtype != LNMOD_F32) return LNMOD_EINVAL;
     if (total < 0 || total >= (int64_t(1) << 31)) return LNMOD_EINVAL;

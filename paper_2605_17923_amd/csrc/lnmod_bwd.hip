@@ -153,9 +153,11 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     r.dshift = dshift;
     r.dscale = dscale;
     r.seg = a.seg;
+    r.T = p.T;
     r.rows_per_block = a.rows_per_block;
     r.D = a.D;
-    const dim3 grid(static_cast<unsigned>((p.D + kWave - 1) / kWave), 2, static_cast<unsigned>(p.nseg));
+    r.dblocks = static_cast<int32_t>((p.D + kWave - 1) / kWave);
+    const dim3 grid(static_cast<unsigned>(p.nseg * 2 * r.dblocks));
     hipLaunchKernelGGL(bwd_reduce_kernel<0>, grid, dim3(kReduceWaves * kWave), 0, st, r);
     return hipGetLastError();
 }

@@ -492,11 +492,10 @@ void bwd_seg_kernel(const BwdArgs a) {
             // pass 1 over the registers: row sums for dx and the running dshift/dscale sums.
             // xhat and g are not kept: they are rebuilt from the packed registers in pass 2,
             // which costs a few ALU operations and saves the registers that occupancy needs.
-            float c1[R], c2[R], nmr[R];
+            float c1[R], c2[R];
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 float p1 = 0.0f, p2 = 0.0f;
-                nmr[j] = -mu[j] * rs[j];
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) {
                     float dyv[E], xv[E];
@@ -504,7 +503,9 @@ void bwd_seg_kernel(const BwdArgs a) {
                     io::unpack(rx[j][i], xv);
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
-                        const float h = xv[e] * rs[j] + nmr[j];    // (x - mean) * rstd
+                        // xhat as (x - mean) * rstd, not x*rstd - mean*rstd: the latter loses every digit
+                        // on (near-)constant rows, where rstd is as large as 1/sqrt(eps)
+                        const float h = (xv[e] - mu[j]) * rs[j];
                         const float gg = dyv[e] * A[i][e];
                         p1 += gg;
                         p2 += gg * h;
@@ -565,7 +566,7 @@ void bwd_seg_kernel(const BwdArgs a) {
                             io::unpack(rx[j][i], xv);
 #pragma unroll
                             for (int e = 0; e < E; ++e) {
-                                const float h = xv[e] * rs[j] + nmr[j];
+                                const float h = (xv[e] - mu[j]) * rs[j];
                                 o[e] = (dyv[e] * A[i][e]) * rs[j] - k1 - h * k2;
                             }
                             store16_u(a.dx, row * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u, io::pack(o));
@@ -602,22 +603,28 @@ struct ReduceArgs {
     float* dshift;           // [nseg, D]
     float* dscale;
     Segments seg;
+    int64_t T;
     int64_t rows_per_block;
     int32_t D;
+    int32_t dblocks;         // ceil(D / 64)
 };
 
 constexpr int kReduceWaves = 16;
 
 // (a template only so that the header can be included in several translation units)
+// grid.x = nseg * 2 * dblocks, decoded as (segment, dshift|dscale, block of 64 features)
 template <int kUnused = 0>
 __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const ReduceArgs a) {
     __shared__ float red[kReduceWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int d = blockIdx.x * kWave + lane;
-    const int which = blockIdx.y;                 // 0: dshift, 1: dscale
-    const int64_t m = blockIdx.z;
-    const int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
+    const int64_t bid = blockIdx.x;
+    const int d = static_cast<int>(bid % a.dblocks) * kWave + lane;
+    const int which = static_cast<int>((bid / a.dblocks) & 1);      // 0: dshift, 1: dscale
+    const int64_t m = bid / (2 * static_cast<int64_t>(a.dblocks));
+    int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
+    if (n0 < 0) n0 = 0;                       // a malformed table must not lead outside ws
+    if (n1 > a.T) n1 = a.T;
     float acc = 0.0f;
     if (n1 > n0 && d < a.D) {
         const int64_t b_lo = n0 / a.rows_per_block, b_hi = (n1 - 1) / a.rows_per_block;
@@ -654,7 +661,6 @@ void bwd_tok_kernel(const BwdArgs a) {
     for (int64_t row = r0 + wave; row < r1; row += WPB) {
         const int64_t base = row * row_bytes;
         const float mu = a.mean[row], rs = a.rstd[row];
-        const float nmr = -mu * rs;
         u32x4 rdy[VPL], rx[VPL], rsc[VPL];
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
@@ -676,7 +682,7 @@ void bwd_tok_kernel(const BwdArgs a) {
             io::unpack(rsc[i], sc);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                const float h = xv[e] * rs + nmr;
+                const float h = (xv[e] - mu) * rs;
                 const float gg = dyv[e] * (1.0f + sc[e]);
                 p1 += gg;
                 p2 += gg * h;
@@ -698,7 +704,7 @@ void bwd_tok_kernel(const BwdArgs a) {
                 io::unpack(rsc[i], sc);
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
-                    const float h = xv[e] * rs + nmr;
+                    const float h = (xv[e] - mu) * rs;
                     o[e] = (dyv[e] * (1.0f + sc[e])) * rs - k1 - h * k2;
                     ds[e] = dyv[e] * h;
                 }

@@ -6,7 +6,10 @@ fp32 I/O 1e-5 relative; mean/rstd 1e-5 relative), read as follows:
   bf16 tensors   rel-L2 <= 4e-3 and, element by element, |err| <= 2e-2 + 2^-8 |ref|: the plain
                  2e-2 bound cannot hold where |ref| >= 8, because rounding the exact result to
                  bf16 already moves it by up to 2^-9 |ref| there.  In addition every GPU value
-                 must lie within one bf16 ulp of the correctly rounded reference.
+                 must lie within one bf16 ulp of the correctly rounded reference, plus the
+                 fp32-level absolute slack 1e-5 max|ref| (a value that cancellation made tiny,
+                 such as a dx entry near zero, carries the absolute fp32 error of its operands,
+                 which can exceed the ulp of the tiny result).
   fp32 tensors   rel-L2 <= 1e-5 and max|err| <= 1e-5 max|ref| (also used for the float32
                  dshift/dscale sums of the bf16 workloads).
   rstd           element-wise relative error <= 1e-5.
@@ -61,7 +64,7 @@ def check_io_tensor(name, got_t, ref64, dtype):
             name, int(bad.sum()), float(err.max()), float(np.abs(ref64).ravel()[err.argmax()]))
         rounded = bf16_round(ref64)
         ulp = bf16_ulp(rounded)
-        off = np.abs(got - rounded) > ulp * 1.0001
+        off = np.abs(got - rounded) > ulp * 1.0001 + 1e-5 * float(np.abs(ref64).max())
         assert not off.any(), "%s: %d elements more than one bf16 ulp from the rounded reference" % (
             name, int(off.sum()))
     else:
