@@ -31,11 +31,15 @@ int64_t total_tokens(int64_t B, int64_t S) {
 }
 
 size_t workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
-    // grid of the widest split over both dtypes, plus one extra slot per segment
-    int64_t blocks = lnmod::bwd_num_blocks(T, D, LNMOD_BF16);
-    const int64_t b2 = lnmod::bwd_num_blocks(T, D, LNMOD_F32);
-    if (b2 > blocks) blocks = b2;
-    return static_cast<size_t>(blocks + nseg) * 2u * static_cast<size_t>(D) * sizeof(float);
+    // partial-sum slots of the plan with more of them (the dtype is not an argument of the query)
+    int64_t slots = 0;
+    for (int dtype = 0; dtype < 2; ++dtype) {
+        if (D % (dtype == 0 ? 8 : 4) != 0) continue;
+        const lnmod::RowPlan pl = lnmod::bwd_plan(T, nseg, D, dtype);
+        const int64_t s = lnmod::bwd_slots(pl, nseg);
+        if (s > slots) slots = s;
+    }
+    return static_cast<size_t>(slots) * 2u * static_cast<size_t>(D) * sizeof(float);
 }
 
 int forward_impl(const void* x, const void* shift, const void* scale, const int32_t* cu,

@@ -8,32 +8,41 @@ namespace {
 
 constexpr int kTokWaves = 4;
 
-// How a row of `nchunks` 16-byte chunks is split: K waves per row, VPL chunks per lane.
+// How a row of `nchunks` 16-byte chunks is split: K waves per row, VPL chunks per lane, R rows
+// per block and step.  A lane keeps about 16 features (up to 24 when one wave can take the
+// whole row, which needs no barrier at all); longer rows are shared by more waves.
 struct Split {
     int K;
     int VPL;
 };
 
-// bf16: 2 chunks (16 features) per lane; fp32: 4 chunks (16 features) per lane; as many waves
-// as the row needs.  Small rows use fewer chunks per lane instead of idle lanes.
 Split choose_split(int nchunks, int dtype) {
-    const int vpl_full = dtype == 0 ? 2 : 4;
-    int vpl = vpl_full;
-    while (vpl > 1 && nchunks <= (vpl / 2) * kWave) vpl /= 2;
-    int k = (nchunks + vpl * kWave - 1) / (vpl * kWave);
+    const int per_feat16 = dtype == 0 ? 2 : 4;          // chunks holding 16 features
+    const int solo_max = dtype == 0 ? 3 : 6;            // chunks per lane a single wave may take
+    const int need = (nchunks + kWave - 1) / kWave;
+    if (need <= solo_max) {
+        int vpl = need;
+        if (dtype == 1 && vpl == 5) vpl = 6;            // instantiated: 1, 2, 3, 4, 6
+        return {1, vpl};
+    }
+    int k = (nchunks + per_feat16 * kWave - 1) / (per_feat16 * kWave);
     if (k == 7) k = 8;
-    return {k, vpl};
+    return {k, per_feat16};
 }
 
-// Blocks per CU so that about 16 waves share a CU.
+// With the software pipeline about 5 or 6 waves per CU, each with 20 to 40 KB of loads in
+// flight, reach the highest HBM bandwidth; more concurrent waves lower it.
 int blocks_per_cu(int K) {
-    int b = 16 / K;
+    if (K == 1) return 4;
+    const int b = 6 / K;
     return b < 1 ? 1 : b;
 }
 
-template <typename Tag, int VPL, int K>
-void go_seg(BwdArgs a, int64_t blocks, hipStream_t st) {
-    constexpr int R = 2;
+// Rows per block and step: one row when a row is long enough to fill the pipeline by itself.
+int rows_per_step(int K, int64_t row_bytes) { return (K > 1 && row_bytes >= 8192) ? 1 : 2; }
+
+template <typename Tag, int VPL, int K, int R>
+void go_seg_r(const BwdArgs& a, int64_t blocks, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
     if (a.nchunks == K * VPL * kWave)
         hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, true>), grid, block, 0, st, a);
@@ -41,27 +50,43 @@ void go_seg(BwdArgs a, int64_t blocks, hipStream_t st) {
         hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, false>), grid, block, 0, st, a);
 }
 
+template <typename Tag, int VPL, int K>
+void go_seg(const BwdArgs& a, int R, int64_t blocks, hipStream_t st) {
+    if (K > 1 && R == 1) go_seg_r<Tag, VPL, K, 1>(a, blocks, st);
+    else go_seg_r<Tag, VPL, K, 2>(a, blocks, st);
+}
+
+// rows wider than one wave: VPL is fixed by the dtype, K varies
 template <typename Tag, int VPL>
-void go_seg_k(const BwdArgs& a, int K, int64_t blocks, hipStream_t st) {
+void go_seg_k(const BwdArgs& a, int K, int R, int64_t blocks, hipStream_t st) {
     switch (K) {
-        case 1: go_seg<Tag, VPL, 1>(a, blocks, st); break;
-        case 2: go_seg<Tag, VPL, 2>(a, blocks, st); break;
-        case 3: go_seg<Tag, VPL, 3>(a, blocks, st); break;
-        case 4: go_seg<Tag, VPL, 4>(a, blocks, st); break;
-        case 5: go_seg<Tag, VPL, 5>(a, blocks, st); break;
-        case 6: go_seg<Tag, VPL, 6>(a, blocks, st); break;
-        default: go_seg<Tag, VPL, 8>(a, blocks, st); break;
+        case 2: go_seg<Tag, VPL, 2>(a, R, blocks, st); break;
+        case 3: go_seg<Tag, VPL, 3>(a, R, blocks, st); break;
+        case 4: go_seg<Tag, VPL, 4>(a, R, blocks, st); break;
+        case 5: go_seg<Tag, VPL, 5>(a, R, blocks, st); break;
+        case 6: go_seg<Tag, VPL, 6>(a, R, blocks, st); break;
+        default: go_seg<Tag, VPL, 8>(a, R, blocks, st); break;
+    }
+}
+
+// rows one wave takes alone (two rows per step)
+template <typename Tag>
+void go_seg_solo(const BwdArgs& a, int VPL, int64_t blocks, hipStream_t st) {
+    switch (VPL) {
+        case 1: go_seg<Tag, 1, 1>(a, 2, blocks, st); break;
+        case 2: go_seg<Tag, 2, 1>(a, 2, blocks, st); break;
+        case 3: go_seg<Tag, 3, 1>(a, 2, blocks, st); break;
+        case 4: go_seg<Tag, 4, 1>(a, 2, blocks, st); break;
+        default: go_seg<Tag, 6, 1>(a, 2, blocks, st); break;
     }
 }
 
 template <typename Tag, int VPL>
 void go_tok(BwdArgs a, hipStream_t st) {
     int64_t blocks = (a.T + kTokWaves - 1) / kTokWaves;
-    const int64_t cap = static_cast<int64_t>(kNumCU) * 8;
+    const int64_t cap = static_cast<int64_t>(kNumCU) * (a.nchunks >= 384 ? 2 : 4);
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    a.rows_per_block = (a.T + blocks - 1) / blocks;
-    blocks = (a.T + a.rows_per_block - 1) / a.rows_per_block;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kTokWaves * kWave);
     if (a.nchunks == VPL * kWave)
         hipLaunchKernelGGL((bwd_tok_kernel<Tag, VPL, kTokWaves, true>), grid, block, 0, st, a);
@@ -98,7 +123,8 @@ BwdArgs make_args(const Problem& p, const void* dy, const void* x, const void* s
     a.ws = ws;
     a.seg = Segments{p.cu, p.S, p.nseg};
     a.T = p.T;
-    a.rows_per_block = 0;
+    a.rows_per_cluster = 0;
+    a.nb = 1;
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
@@ -113,20 +139,11 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float* p, int64_t n) {
 
 }  // namespace
 
-int64_t bwd_num_blocks(int64_t T, int64_t D, int dtype) {
-    if (T <= 0) return 0;
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
     const Split sp = choose_split(static_cast<int>(D / E), dtype);
-    int64_t blocks = static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K);
-    if (blocks > kMaxBwdBlocks) blocks = kMaxBwdBlocks;
-    if (blocks > T) blocks = T;
-    const int64_t rpb = (T + blocks - 1) / blocks;
-    return (T + rpb - 1) / rpb;
-}
-
-int64_t bwd_rows_per_block(int64_t T, int64_t D, int dtype) {
-    const int64_t blocks = bwd_num_blocks(T, D, dtype);
-    return blocks > 0 ? (T + blocks - 1) / blocks : 1;
+    const int R = rows_per_step(sp.K, D * (dtype == 0 ? 2 : 4));
+    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K), R, 90);
 }
 
 hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const void* scale,
@@ -135,15 +152,17 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
     const Split sp = choose_split(a.nchunks, p.dtype);
-    const int64_t blocks = bwd_num_blocks(p.T, p.D, p.dtype);
-    a.rows_per_block = bwd_rows_per_block(p.T, p.D, p.dtype);
+    const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype);
+    const int64_t blocks = pl.blocks;
+    a.rows_per_cluster = pl.rows_per_cluster;
+    a.nb = pl.nb;
+    const int R = rows_per_step(sp.K, p.D * (p.dtype == 0 ? 2 : 4));
     if (p.dtype == 0) {
-        if (sp.VPL == 1) go_seg_k<bf16_io, 1>(a, sp.K, blocks, st);
-        else go_seg_k<bf16_io, 2>(a, sp.K, blocks, st);
+        if (sp.K == 1) go_seg_solo<bf16_io>(a, sp.VPL, blocks, st);
+        else go_seg_k<bf16_io, 2>(a, sp.K, R, blocks, st);
     } else {
-        if (sp.VPL == 1) go_seg_k<f32_io, 1>(a, sp.K, blocks, st);
-        else if (sp.VPL == 2) go_seg_k<f32_io, 2>(a, sp.K, blocks, st);
-        else go_seg_k<f32_io, 4>(a, sp.K, blocks, st);
+        if (sp.K == 1) go_seg_solo<f32_io>(a, sp.VPL, blocks, st);
+        else go_seg_k<f32_io, 4>(a, sp.K, R, blocks, st);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -154,7 +173,8 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     r.dscale = dscale;
     r.seg = a.seg;
     r.T = p.T;
-    r.rows_per_block = a.rows_per_block;
+    r.rows_per_cluster = a.rows_per_cluster;
+    r.nb = a.nb;
     r.D = a.D;
     r.dblocks = static_cast<int32_t>((p.D + kWave - 1) / kWave);
     const dim3 grid(static_cast<unsigned>(p.nseg * 2 * r.dblocks));

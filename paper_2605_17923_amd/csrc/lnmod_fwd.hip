@@ -9,20 +9,15 @@ namespace {
 constexpr int kFwdWaves = 4;                    // waves (= rows in flight) per block
 constexpr size_t kLdsPerCU = 160 * 1024;
 
-struct RowGrid {
-    int64_t blocks;
-    int64_t rows_per_block;
-};
-
-// Equal contiguous row ranges, never more blocks than can be resident at once, so every CU
-// finishes at the same time instead of leaving a partial last round of blocks.
-RowGrid row_grid(int64_t T, int waves_per_block, int blocks_per_cu) {
-    int64_t blocks = (T + waves_per_block - 1) / waves_per_block;
-    const int64_t cap = static_cast<int64_t>(kNumCU) * blocks_per_cu;
-    if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
-    const int64_t rpb = (T + blocks - 1) / blocks;
-    return {(T + rpb - 1) / rpb, rpb};
+// Resident blocks per CU: 8 waves per CU stream best whatever the row length (more concurrent
+// waves lower the achieved HBM bandwidth), so 2 blocks of 4 waves, LDS permitting.
+int fwd_blocks_per_cu(size_t lds_bytes) {
+    int bpc = 2;
+    if (lds_bytes) {
+        const int fit = static_cast<int>((kLdsPerCU - 8 * 1024) / lds_bytes);
+        if (bpc > fit) bpc = fit;
+    }
+    return bpc < 1 ? 1 : bpc;
 }
 
 FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
@@ -36,7 +31,8 @@ FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void
     a.rstd = rstd;
     a.seg = Segments{p.cu, p.S, p.nseg};
     a.T = p.T;
-    a.rows_per_block = 0;
+    a.rows_per_cluster = 0;
+    a.nb = 1;
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
@@ -48,12 +44,11 @@ template <typename Tag, int VPL>
 void go_seg(FwdArgs a, hipStream_t st) {
     constexpr int E = IO<Tag>::E;
     const size_t lds = static_cast<size_t>(2) * VPL * kWave * E * sizeof(float);
-    int bpc = static_cast<int>((kLdsPerCU - 8 * 1024) / lds);
-    if (bpc > 8) bpc = 8;
-    if (bpc < 1) bpc = 1;
-    const RowGrid g = row_grid(a.T, kFwdWaves, bpc);
-    a.rows_per_block = g.rows_per_block;
-    const dim3 grid(static_cast<unsigned>(g.blocks)), block(kFwdWaves * kWave);
+    const int bpc = fwd_blocks_per_cu(lds);
+    const RowPlan pl = plan_rows(a.T, a.seg.nseg, static_cast<int64_t>(kNumCU) * bpc, kFwdWaves, 20);
+    a.rows_per_cluster = pl.rows_per_cluster;
+    a.nb = pl.nb;
+    const dim3 grid(static_cast<unsigned>(pl.blocks)), block(kFwdWaves * kWave);
     if (a.nchunks == VPL * kWave)
         hipLaunchKernelGGL((fwd_seg_kernel<Tag, VPL, kFwdWaves, true>), grid, block, lds, st, a);
     else
@@ -62,9 +57,10 @@ void go_seg(FwdArgs a, hipStream_t st) {
 
 template <typename Tag, int VPL>
 void go_tok(FwdArgs a, hipStream_t st) {
-    const RowGrid g = row_grid(a.T, kFwdWaves, 8);
-    a.rows_per_block = g.rows_per_block;
-    const dim3 grid(static_cast<unsigned>(g.blocks)), block(kFwdWaves * kWave);
+    const int bpc = fwd_blocks_per_cu(0);
+    int64_t blocks = (a.T + kFwdWaves - 1) / kFwdWaves;
+    if (blocks > static_cast<int64_t>(kNumCU) * bpc) blocks = static_cast<int64_t>(kNumCU) * bpc;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kFwdWaves * kWave);
     if (a.nchunks == VPL * kWave)
         hipLaunchKernelGGL((fwd_tok_kernel<Tag, VPL, kFwdWaves, true>), grid, block, 0, st, a);
     else

@@ -28,10 +28,13 @@
 #include <stdint.h>
 
 #ifndef LNMOD_NT_LOAD
-#define LNMOD_NT_LOAD 0
+#define LNMOD_NT_LOAD 1
+#endif
+#ifndef LNMOD_MAX_WAVES_PER_EU
+#define LNMOD_MAX_WAVES_PER_EU 3   // the launches keep 2 to 3 waves per SIMD resident, not more
 #endif
 #ifndef LNMOD_NT_STORE
-#define LNMOD_NT_STORE 0
+#define LNMOD_NT_STORE 1
 #endif
 
 namespace lnmod {
@@ -49,13 +52,14 @@ constexpr int kWave = 64;
 // wave fills the SIMD and nothing hides the HBM latency.
 constexpr int row_waves_per_eu(int vpl, int elems_per_chunk, int rows_live = 1) {
     const int cost = vpl * (elems_per_chunk * rows_live + 2);
-    return cost <= 40 ? 8 : cost <= 50 ? 6 : cost <= 60 ? 5 : cost <= 100 ? 4 : cost <= 130 ? 3 : 2;
+    const int w = cost <= 40 ? 8 : cost <= 50 ? 6 : cost <= 60 ? 5 : cost <= 100 ? 4 : cost <= 130 ? 3 : 2;
+    return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w;
 }
 // Kernels that keep `streams` packed 16-byte registers per chunk and rebuild fp32 values per pass.
 constexpr int tok_waves_per_eu(int vpl, int streams) {
     const int regs = vpl * (4 * streams + 1) + 40;
     const int w = 512 / regs;
-    return w > 8 ? 8 : w < 1 ? 1 : w;
+    return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }
 #define LNMOD_OCCUPANCY(W) __attribute__((amdgpu_waves_per_eu(W)))
 
@@ -202,15 +206,16 @@ struct FwdArgs {
     float* rstd;
     Segments seg;
     int64_t T;               // total token rows
-    int64_t rows_per_block;
+    int64_t rows_per_cluster; // rows of the contiguous region one cluster of blocks streams through
+    int32_t nb;              // blocks per cluster (per-token kernels: unused)
     int32_t D;
     int32_t nchunks;         // D / E
     float eps;
     float inv_D;
 };
 
-template <typename Tag, int VPL, int WPB, bool EXACT>
-__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(row_waves_per_eu(VPL, IO<Tag>::E))
+template <typename Tag, int VPL, int WPB, bool EXACT, bool PF = true>
+__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(row_waves_per_eu(VPL, IO<Tag>::E + (PF ? 4 : 0)))
 void fwd_seg_kernel(const FwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
@@ -222,8 +227,12 @@ void fwd_seg_kernel(const FwdArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
 
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
+    // cluster of a.nb blocks <-> contiguous region of rows; inside the region the cluster's
+    // waves take consecutive rows, so at any moment the cluster streams through one window
+    const int64_t cluster = blockIdx.x / a.nb;
+    const int64_t member = blockIdx.x - cluster * a.nb;
+    int64_t r0 = cluster * a.rows_per_cluster;
+    int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
 
     while (r0 < r1) {
@@ -250,14 +259,31 @@ void fwd_seg_kernel(const FwdArgs a) {
         }
         __syncthreads();
 
-        for (int64_t row = r0 + wave; row < stop; row += WPB) {
-            const int64_t base = row * row_bytes;
-            u32x4 raw[VPL];
+        // Software pipeline: the wave requests its next row before it works on the current one,
+        // so a few waves per CU keep the memory system busy (few, deep streams reach a higher
+        // HBM bandwidth than many shallow ones).
+        auto fetch = [&](int64_t row, u32x4 (&q)[VPL]) {
 #pragma unroll
             for (int i = 0; i < VPL; ++i) {
                 const int c = i * kWave + lane;
-                if (EXACT || c < a.nchunks) raw[i] = load16(a.x, base, static_cast<uint32_t>(c) * 16u);
-                else raw[i] = u32x4{0u, 0u, 0u, 0u};
+                if (row < stop && (EXACT || c < a.nchunks))
+                    q[i] = load16(a.x, row * row_bytes, static_cast<uint32_t>(c) * 16u);
+                else
+                    q[i] = u32x4{0u, 0u, 0u, 0u};
+            }
+        };
+        const int64_t row_step = static_cast<int64_t>(a.nb) * WPB;
+        u32x4 raw[VPL];
+        if (PF) fetch(r0 + member * WPB + wave, raw);
+
+        for (int64_t row = r0 + member * WPB + wave; row < stop; row += row_step) {
+            const int64_t base = row * row_bytes;
+            u32x4 nxt[VPL];
+            if (PF) {
+                fetch(row + row_step, nxt);
+                __builtin_amdgcn_sched_barrier(0);           // keep the requests up here
+            } else {
+                fetch(row, raw);
             }
             float v[VPL][E];
             float s = 0.0f;
@@ -302,6 +328,10 @@ void fwd_seg_kernel(const FwdArgs a) {
                 // branch-free body the scheduler otherwise issues all of them first and spills
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (PF) {
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) raw[i] = nxt[i];
+            }
         }
         r0 = stop;
     }
@@ -326,11 +356,12 @@ void fwd_tok_kernel(const FwdArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
 
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
-    if (r1 > a.T) r1 = a.T;
+    // all waves of the grid take consecutive rows: the launch streams through one moving window
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
+    const int64_t r1 = a.T;
+    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
 
-    for (int64_t row = r0 + wave; row < r1; row += WPB) {
+    for (int64_t row = r0 + wave; row < r1; row += row_step) {
         const int64_t base = row * row_bytes;
         u32x4 raw[VPL], rsc[VPL], rsh[VPL];
 #pragma unroll
@@ -410,7 +441,8 @@ struct BwdArgs {
     float* ws;               // [nslots][2][D] fp32 partial sums
     Segments seg;
     int64_t T;
-    int64_t rows_per_block;
+    int64_t rows_per_cluster;
+    int32_t nb;              // blocks per cluster
     int32_t D;
     int32_t nchunks;
     float inv_D;
@@ -421,11 +453,11 @@ constexpr int bwd_waves_per_eu(int vpl, int elems_per_chunk, int rows) {
     // and x with their addresses; plus unpack temporaries and loop state
     const int regs = vpl * (3 * elems_per_chunk + 10 * rows) + 28;
     const int w = 512 / regs;
-    return w > 8 ? 8 : w < 1 ? 1 : w;
+    return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }
 
-template <typename Tag, int VPL, int K, int R, bool EXACT>
-__global__ __launch_bounds__(K* kWave) LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, R))
+template <typename Tag, int VPL, int K, int R, bool EXACT, bool PF = true>
+__global__ __launch_bounds__(K* kWave) LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, PF ? 2 * R : R))
 void bwd_seg_kernel(const BwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
@@ -443,8 +475,10 @@ void bwd_seg_kernel(const BwdArgs a) {
         ok[i] = EXACT || chunk[i] < a.nchunks;
     }
 
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
+    const int64_t cluster = blockIdx.x / a.nb;
+    const int64_t member = blockIdx.x - cluster * a.nb;
+    int64_t r0 = cluster * a.rows_per_cluster;
+    int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
     int buf = 0;
 
@@ -468,26 +502,43 @@ void bwd_seg_kernel(const BwdArgs a) {
             }
         }
 
-        for (int64_t base = r0; base < stop; base += R) {
-            u32x4 rdy[R][VPL], rx[R][VPL];
-            float mu[R], rs[R];
+        // Software pipeline: the packed dy/x of the block's next step are requested before the
+        // current step is computed, so every block keeps loads in flight while it does
+        // arithmetic, waits at its barrier and stores.
+        auto fetch = [&](int64_t base, u32x4 (&qdy)[R][VPL], u32x4 (&qx)[R][VPL], float (&qmu)[R],
+                         float (&qrs)[R]) {
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int64_t row = base + j;
                 const bool live = row < stop;
-                mu[j] = live ? a.mean[row] : 0.0f;
-                rs[j] = live ? a.rstd[row] : 0.0f;
+                qmu[j] = live ? a.mean[row] : 0.0f;
+                qrs[j] = live ? a.rstd[row] : 0.0f;
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) {
                     if (live && ok[i]) {
                         const uint32_t lo = static_cast<uint32_t>(chunk[i]) * 16u;
-                        rdy[j][i] = load16_u(a.dy, row * row_bytes, lo);
-                        rx[j][i] = load16_u(a.x, row * row_bytes, lo);
+                        qdy[j][i] = load16_u(a.dy, row * row_bytes, lo);
+                        qx[j][i] = load16_u(a.x, row * row_bytes, lo);
                     } else {
-                        rdy[j][i] = u32x4{0u, 0u, 0u, 0u};
-                        rx[j][i] = u32x4{0u, 0u, 0u, 0u};
+                        qdy[j][i] = u32x4{0u, 0u, 0u, 0u};
+                        qx[j][i] = u32x4{0u, 0u, 0u, 0u};
                     }
                 }
+            }
+        };
+        const int64_t step = static_cast<int64_t>(a.nb) * R;
+        u32x4 rdy[R][VPL], rx[R][VPL];
+        float mu[R], rs[R];
+        if (PF) fetch(r0 + member * R, rdy, rx, mu, rs);     // rows at or beyond `stop` read as zeros
+
+        for (int64_t base = r0 + member * R; base < stop; base += step) {
+            u32x4 ndy[R][VPL], nx[R][VPL];
+            float nmu[R], nrs[R];
+            if (PF) {
+                fetch(base + step, ndy, nx, nmu, nrs);
+                __builtin_amdgcn_sched_barrier(0);           // keep the requests up here
+            } else {
+                fetch(base, rdy, rx, mu, rs);
             }
             // pass 1 over the registers: row sums for dx and the running dshift/dscale sums.
             // xhat and g are not kept: they are rebuilt from the packed registers in pass 2,
@@ -575,10 +626,22 @@ void bwd_seg_kernel(const BwdArgs a) {
                     }
                 }
             }
+            if (PF) {
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    mu[j] = nmu[j];
+                    rs[j] = nrs[j];
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) {
+                        rdy[j][i] = ndy[j][i];
+                        rx[j][i] = nx[j][i];
+                    }
+                }
+            }
         }
 
         // this block's partial sums for segment m
-        float* slot = a.ws + (static_cast<int64_t>(blockIdx.x) + m) * 2 * a.D;
+        float* slot = a.ws + ((cluster + m) * a.nb + member) * 2 * a.D;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             if (ok[i]) {
@@ -604,7 +667,8 @@ struct ReduceArgs {
     float* dscale;
     Segments seg;
     int64_t T;
-    int64_t rows_per_block;
+    int64_t rows_per_cluster;
+    int32_t nb;              // blocks per cluster = partial slots per (cluster, segment)
     int32_t D;
     int32_t dblocks;         // ceil(D / 64)
 };
@@ -627,9 +691,11 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const R
     if (n1 > a.T) n1 = a.T;
     float acc = 0.0f;
     if (n1 > n0 && d < a.D) {
-        const int64_t b_lo = n0 / a.rows_per_block, b_hi = (n1 - 1) / a.rows_per_block;
-        for (int64_t b = b_lo + wave; b <= b_hi; b += kReduceWaves)
-            acc += a.ws[((b + m) * 2 + which) * a.D + d];
+        // clusters c_lo..c_hi touch this segment; (cluster c, segment m) owns slots (c+m)*nb ..
+        const int64_t c_lo = n0 / a.rows_per_cluster, c_hi = (n1 - 1) / a.rows_per_cluster;
+        const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
+        for (int64_t sl = s_lo + wave; sl < s_hi; sl += kReduceWaves)
+            acc += a.ws[(sl * 2 + which) * a.D + d];
     }
     red[wave][lane] = acc;
     __syncthreads();
@@ -654,11 +720,12 @@ void bwd_tok_kernel(const BwdArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
 
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
-    if (r1 > a.T) r1 = a.T;
+    // all waves of the grid take consecutive rows: the launch streams through one moving window
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
+    const int64_t r1 = a.T;
+    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
 
-    for (int64_t row = r0 + wave; row < r1; row += WPB) {
+    for (int64_t row = r0 + wave; row < r1; row += row_step) {
         const int64_t base = row * row_bytes;
         const float mu = a.mean[row], rs = a.rstd[row];
         u32x4 rdy[VPL], rx[VPL], rsc[VPL];
@@ -730,10 +797,11 @@ void unfused_ln_kernel(const FwdArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
-    if (r1 > a.T) r1 = a.T;
-    for (int64_t row = r0 + wave; row < r1; row += WPB) {
+    // all waves of the grid take consecutive rows: the launch streams through one moving window
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
+    const int64_t r1 = a.T;
+    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
+    for (int64_t row = r0 + wave; row < r1; row += row_step) {
         const int64_t base = row * row_bytes;
         u32x4 raw[VPL];
 #pragma unroll
@@ -787,10 +855,11 @@ __global__ __launch_bounds__(WPB* kWave) void unfused_mod_kernel(const FwdArgs a
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-    int64_t r0 = static_cast<int64_t>(blockIdx.x) * a.rows_per_block;
-    int64_t r1 = r0 + a.rows_per_block;
-    if (r1 > a.T) r1 = a.T;
-    for (int64_t row = r0 + wave; row < r1; row += WPB) {
+    // all waves of the grid take consecutive rows: the launch streams through one moving window
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
+    const int64_t r1 = a.T;
+    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
+    for (int64_t row = r0 + wave; row < r1; row += row_step) {
         const int64_t m = find_segment(a.seg, row);
         const int64_t base = row * row_bytes;
 #pragma unroll
@@ -809,12 +878,42 @@ __global__ __launch_bounds__(WPB* kWave) void unfused_mod_kernel(const FwdArgs a
     }
 }
 
+// Plain copy in the same access pattern as the row kernels: every wave moves 4 KB per step
+// with 16-byte nontemporal accesses, the waves of the grid take consecutive 4 KB pieces, and
+// the next piece is requested before the current one is stored.
+constexpr int kCopyWaves = 4;
+constexpr int kCopyVecs = 4;     // 16-byte vectors per lane and step
+
 template <int kUnused = 0>
-__global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
-                                                      int64_t nvec) {
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec; i += stride)
-        dst[i] = src[i];
+__global__ __launch_bounds__(kCopyWaves* kWave) void copy16_kernel(const u32x4* __restrict__ src,
+                                                                   u32x4* __restrict__ dst, int64_t nvec) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int64_t kPiece = static_cast<int64_t>(kCopyVecs) * kWave;
+    const int64_t pieces = nvec / kPiece;
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kCopyWaves;
+    auto fetch = [&](int64_t piece, u32x4 (&q)[kCopyVecs]) {
+#pragma unroll
+        for (int i = 0; i < kCopyVecs; ++i) {
+            if (piece < pieces) q[i] = __builtin_nontemporal_load(src + piece * kPiece + i * kWave + lane);
+            else q[i] = u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    int64_t piece = static_cast<int64_t>(blockIdx.x) * kCopyWaves + wave;
+    u32x4 cur[kCopyVecs];
+    fetch(piece, cur);
+    for (; piece < pieces; piece += step) {
+        u32x4 nxt[kCopyVecs];
+        fetch(piece + step, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kCopyVecs; ++i) __builtin_nontemporal_store(cur[i], dst + piece * kPiece + i * kWave + lane);
+#pragma unroll
+        for (int i = 0; i < kCopyVecs; ++i) cur[i] = nxt[i];
+    }
+    if (blockIdx.x == 0) {                       // fewer than one piece left over
+        for (int64_t i = pieces * kPiece + threadIdx.x; i < nvec; i += kCopyWaves * kWave) dst[i] = src[i];
+    }
 }
 
 }  // namespace lnmod

@@ -9,7 +9,6 @@ namespace lnmod {
 
 constexpr int kNumCU = 256;            // MI355X: 8 XCDs x 32 CUs
 constexpr int64_t kMaxD = 8192;
-constexpr int kMaxBwdBlocks = 2048;    // upper bound of the backward grid (sizes the workspace)
 
 struct Problem {
     int dtype;                 // LNMOD_BF16 / LNMOD_F32
@@ -21,10 +20,53 @@ struct Problem {
     float eps;
 };
 
-// Rows every backward block owns for this problem; the same function sizes the workspace,
-// drives the main kernel's grid and tells the second pass which slots belong to a segment.
-int64_t bwd_rows_per_block(int64_t T, int64_t D, int dtype);
-int64_t bwd_num_blocks(int64_t T, int64_t D, int dtype);
+// How the token rows are spread over the grid.  `clusters` groups of `nb` blocks each own one
+// contiguous region of `rows_per_cluster` rows; inside its region a cluster's blocks take
+// consecutive rows, so the cluster streams through one moving window of memory (HBM rewards
+// few concurrent sequential streams far more than one private stream per block).  nb shrinks
+// when there are many segments, because every (cluster, segment) pair costs nb reloads of the
+// modulation rows (forward) or nb partial-sum slots (backward).
+struct RowPlan {
+    int64_t blocks;            // clusters * nb
+    int64_t clusters;
+    int64_t rows_per_cluster;
+    int32_t nb;
+};
+
+// max_blocks: resident blocks wanted; rows_per_step: rows one block takes per iteration;
+// overhead_div: nb * (nseg - 1) is kept below T / overhead_div - blocks.
+inline RowPlan plan_rows(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
+                         int64_t overhead_div) {
+    RowPlan p{0, 0, 1, 1};
+    if (T <= 0) return p;
+    int64_t g = (T + rows_per_step - 1) / rows_per_step;
+    if (g > max_blocks) g = max_blocks;
+    if (g < 1) g = 1;
+    int64_t nb = g;
+    if (nseg > 1) {
+        int64_t budget = T / overhead_div - g;
+        if (budget < 0) budget = 0;
+        nb = budget / (nseg - 1);
+        if (nb > g) nb = g;
+        if (nb < 1) nb = 1;
+        int64_t pow2 = 1;
+        while (pow2 * 2 <= nb) pow2 *= 2;
+        nb = pow2;
+    }
+    int64_t clusters = (g + nb - 1) / nb;
+    const int64_t rpc = (T + clusters - 1) / clusters;
+    clusters = (T + rpc - 1) / rpc;
+    p.blocks = clusters * nb;
+    p.clusters = clusters;
+    p.rows_per_cluster = rpc;
+    p.nb = static_cast<int32_t>(nb);
+    return p;
+}
+
+// The backward's plan for this problem: the same function sizes the workspace, drives the main
+// kernel's grid and tells the second pass which partial-sum slots belong to a segment.
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
+inline int64_t bwd_slots(const RowPlan& p, int64_t nseg) { return (p.clusters + nseg) * p.nb; }
 
 hipError_t launch_fwd_seg(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* y, float* mean, float* rstd, hipStream_t st);

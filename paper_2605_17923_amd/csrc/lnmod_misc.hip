@@ -11,13 +11,9 @@ constexpr int kWaves = 4;
 template <typename Tag, int VPL>
 void go_unfused(FwdArgs ln, FwdArgs mod, hipStream_t st) {
     int64_t blocks = (ln.T + kWaves - 1) / kWaves;
-    const int64_t cap = static_cast<int64_t>(kNumCU) * 8;
+    const int64_t cap = static_cast<int64_t>(kNumCU) * (ln.nchunks >= 512 ? 2 : 4);
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    const int64_t rpb = (ln.T + blocks - 1) / blocks;
-    blocks = (ln.T + rpb - 1) / rpb;
-    ln.rows_per_block = rpb;
-    mod.rows_per_block = rpb;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kWaves * kWave);
     hipLaunchKernelGGL((unfused_ln_kernel<Tag, VPL, kWaves, false>), grid, block, 0, st, ln);
     hipLaunchKernelGGL((unfused_mod_kernel<Tag, VPL, kWaves, false>), grid, block, 0, st, mod);
@@ -53,7 +49,8 @@ hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, co
     ln.rstd = rstd;
     ln.seg = Segments{p.cu, p.S, p.nseg};
     ln.T = p.T;
-    ln.rows_per_block = 0;
+    ln.rows_per_cluster = 0;
+    ln.nb = 1;
     ln.D = static_cast<int32_t>(p.D);
     ln.nchunks = static_cast<int32_t>(p.D / E);
     ln.eps = p.eps;
@@ -72,10 +69,12 @@ hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, co
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
     const int64_t nvec = static_cast<int64_t>(bytes / 16);
     if (nvec == 0) return hipSuccess;
-    int64_t blocks = (nvec + 255) / 256;
-    const int64_t cap = static_cast<int64_t>(kNumCU) * 8;
+    const int64_t pieces = nvec / (kCopyVecs * kWave);
+    int64_t blocks = (pieces + kCopyWaves - 1) / kCopyWaves;
+    const int64_t cap = static_cast<int64_t>(kNumCU) * 2;
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(copy16_kernel<0>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(copy16_kernel<0>, dim3(static_cast<unsigned>(blocks)), dim3(kCopyWaves * kWave), 0, st,
                        static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
     return hipGetLastError();
 }
