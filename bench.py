@@ -78,8 +78,8 @@ def cpu_baseline(D, sample_tokens, repeats=3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-sample-tokens", type=int, default=75600)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
@@ -162,7 +162,7 @@ def main():
         "tokens_per_s": round(T / (ms_per_step * 1e-3)),
         "roofline": roof(bwd_b, bwd_ms, "lnmod_backward = bwd_seg_kernel + bwd_reduce_kernel "
                                         "(durations summed)", MEASURED_TRAFFIC_BYTES["backward"]),
-        "roofline_fwd": roof(fwd_b, fwd_ms, "fwd_seg_kernel", MEASURED_TRAFFIC_BYTES["forward"]),
+        "roofline_fwd": roof(fwd_b, fwd_ms, "fwd_split_kernel", MEASURED_TRAFFIC_BYTES["forward"]),
     }
 
     if not args.no_extras:
@@ -184,43 +184,114 @@ def _time_ms(torch, stream, fn, iters=20, warm=3):
     return sum(a[i].elapsed_time(a[i + 1]) for i in range(iters)) / iters
 
 
+def _gbs(nbytes, ms):
+    return round(nbytes / (ms * 1e-3) / 1e9, 1)
+
+
+def _randn_bf16(torch, g, shape, dev, std=1.0, mean=0.0):
+    return (torch.randn(*shape, generator=g, device=dev) * std + mean).to(torch.bfloat16)
+
+
+def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=None, rotate=1, seed=1):
+    """Forward and backward of one workload shape (bf16), timed with events on the launch stream.
+    `rotate` > 1 cycles through that many independent buffer sets so that a workload smaller
+    than the 256 MB Infinity Cache still streams from HBM."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    T = int(sum(lengths)) if lengths is not None else B * S
+    nseg = len(lengths) if lengths is not None else B
+    per_token = mod == lnmod.LNMOD_PER_TOKEN
+    mrows = T if per_token else nseg
+    sets = []
+    for _ in range(rotate):
+        x = _randn_bf16(torch, g, (T, D), dev)
+        dy = _randn_bf16(torch, g, (T, D), dev)
+        sh = _randn_bf16(torch, g, (mrows, D), dev, 0.1)
+        sc = _randn_bf16(torch, g, (mrows, D), dev, 0.1)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        if per_token:
+            dsh, dsc = torch.empty_like(x), torch.empty_like(x)
+        else:
+            dsh = torch.empty(nseg, D, dtype=torch.float32, device=dev)
+            dsc = torch.empty(nseg, D, dtype=torch.float32, device=dev)
+        sets.append((x, dy, sh, sc, y, dx, dsh, dsc))
+    mean = torch.empty(T, dtype=torch.float32, device=dev)
+    rstd = torch.empty(T, dtype=torch.float32, device=dev)
+    ws = lnmod.workspace(nseg, T, D, dev)
+    cu = None
+    if lengths is not None:
+        import itertools
+        cu = torch.tensor([0] + list(itertools.accumulate(lengths)), dtype=torch.int32, device=dev)
+    state = {"i": 0}
+
+    def pick():
+        state["i"] = (state["i"] + 1) % rotate
+        return sets[state["i"]]
+
+    def fwd():
+        x, dy, sh, sc, y, dx, dsh, dsc = pick()
+        if cu is not None:
+            rc = lnmod.lnmod_forward_varlen(x, sh, sc, cu, nseg, T, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16)
+        else:
+            rc = lnmod.lnmod_forward(x, sh, sc, B, S, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16, mod)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    def bwd():
+        x, dy, sh, sc, y, dx, dsh, dsc = pick()
+        if cu is not None:
+            rc = lnmod.lnmod_backward_varlen(dy, x, None, sc, cu, nseg, T, D, 1e-6, st, mean, rstd, dx, dsh,
+                                             dsc, ws, ws.numel(), lnmod.LNMOD_BF16)
+        else:
+            rc = lnmod.lnmod_backward(dy, x, None, sc, B, S, D, 1e-6, st, mean, rstd, dx, dsh, dsc, ws,
+                                      ws.numel(), lnmod.LNMOD_BF16, mod)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    fwd()
+    torch.cuda.synchronize()
+    f_ms = _time_ms(torch, stream, fwd)
+    b_ms = _time_ms(torch, stream, bwd)
+    mod_bytes = 2 * D * 2                       # shift + scale, or scale + two per-token outputs
+    fwd_b = T * (4 * D + 8) + (T * mod_bytes if per_token else 0)
+    bwd_b = T * (6 * D + 8) + (T * 3 * D * 2 if per_token else 0)
+    return {"workload": name, "tokens": T, "D": D,
+            "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
+            "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
+
+
 def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
     """Context figures: a plain copy as the practical bandwidth ceiling, the unfused two-kernel
-    forward (LayerNorm -> xhat in HBM -> modulate) and the Wan-1.3B-shaped forward."""
+    forward (LayerNorm -> xhat in HBM -> modulate), the other workload shapes and the token
+    counts of the paper's kernel table (Table 2: N = 8k ... 64k) at D = 5120."""
     res = {}
+    dev = x.device
     nbytes = x.numel() * 2
     ms = _time_ms(torch, stream, lambda: lnmod.lnmod_copy(x, y, nbytes, st))
-    res["copy_ceiling_GBs"] = round(2 * nbytes / (ms * 1e-3) / 1e9, 1)
+    res["copy_ceiling_GBs"] = _gbs(2 * nbytes, ms)
     tmp = torch.empty_like(x)
     ms_u = _time_ms(torch, stream, lambda: lnmod.lnmod_unfused_forward(
         x, shift, scale, 1, T, D, 1e-6, st, tmp, y, mean, rstd, lnmod.LNMOD_BF16))
+    ms_f = _time_ms(torch, stream, lambda: lnmod.lnmod_forward(
+        x, shift, scale, 1, T, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16, lnmod.LNMOD_PER_SAMPLE))
     res["unfused_fwd_us"] = round(ms_u * 1e3, 1)
-    res["fused_fwd_us"] = round(fused_fwd_ms * 1e3, 1)
-    res["fused_vs_unfused_fwd_speedup"] = round(ms_u / fused_fwd_ms, 3)
+    res["fused_fwd_us"] = round(ms_f * 1e3, 1)
+    res["fused_vs_unfused_fwd_speedup"] = round(ms_u / ms_f, 3)
     del tmp
-    # configs[1]: bf16 forward, B=1, S=32760, D=1536 (201 MB: fits the 256 MB Infinity Cache, so
-    # three buffer sets are rotated to keep the traffic in HBM)
-    S1, D1 = 32760, 1536
-    g = torch.Generator(device=x.device)
-    g.manual_seed(1002)
-    xs = [torch.randn(S1, D1, generator=g, device=x.device).to(torch.bfloat16) for _ in range(3)]
-    ys = [torch.empty_like(t) for t in xs]
-    sh1 = (0.1 * torch.randn(1, D1, generator=g, device=x.device)).to(torch.bfloat16)
-    sc1 = (0.1 * torch.randn(1, D1, generator=g, device=x.device)).to(torch.bfloat16)
-    m1 = torch.empty(S1, device=x.device)
-    r1 = torch.empty(S1, device=x.device)
-    state = {"i": 0}
-
-    def f1():
-        i = state["i"] = (state["i"] + 1) % 3
-        lnmod.lnmod_forward(xs[i], sh1, sc1, 1, S1, D1, 1e-6, st, ys[i], m1, r1, lnmod.LNMOD_BF16,
-                            lnmod.LNMOD_PER_SAMPLE)
-
-    ms1 = _time_ms(torch, stream, f1, iters=30)
-    b1 = S1 * (4 * D1 + 8)
-    res["config1_fwd"] = {"us": round(ms1 * 1e3, 2), "GBs": round(b1 / (ms1 * 1e-3) / 1e9, 1),
-                          "frac": round(b1 / (ms1 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                          "tokens_per_s": round(S1 / (ms1 * 1e-3))}
+    from paper_2605_17923_amd import synth
+    lengths, _ = synth.varlen_lengths()
+    PS, PT = lnmod.LNMOD_PER_SAMPLE, lnmod.LNMOD_PER_TOKEN
+    res["workloads"] = [
+        _run_workload(lnmod, torch, stream, st, dev, "configs[1] Wan-1.3B B=1 S=32760 D=1536 (3 buffer sets rotated)",
+                      1, 32760, 1536, PS, rotate=3, seed=1002),
+        _run_workload(lnmod, torch, stream, st, dev, "configs[3] per-token B=2 S=32760 D=5120", 2, 32760, 5120, PT,
+                      seed=1004),
+        _run_workload(lnmod, torch, stream, st, dev, "configs[4] varlen 24 segments T=%d D=5120" % sum(lengths),
+                      24, 0, 5120, PS, lengths=lengths, seed=1005),
+    ]
+    grid = []
+    for n in range(8000, 64001, 8000):
+        r = _run_workload(lnmod, torch, stream, st, dev, "N=%d" % n, 1, n, 5120, PS, seed=n)
+        grid.append({"N": n, "fwd_us": r["fwd_us"], "bwd_us": r["bwd_us"]})
+    res["paper_table2_grid_D5120"] = grid
     return res
 
 

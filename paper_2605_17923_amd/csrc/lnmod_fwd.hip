@@ -1,23 +1,20 @@
 // lnmod_fwd.hip -- instantiation and launch of the forward kernels (per-sample / per-segment
-// modulation through LDS, and per-token modulation streamed with x).
+// modulation kept in registers by K waves per row, and per-token modulation streamed with x).
 #include "lnmod_kernels.hpp"
 #include "lnmod_launch.hpp"
 
 namespace lnmod {
 namespace {
 
-constexpr int kFwdWaves = 4;                    // waves (= rows in flight) per block
-constexpr size_t kLdsPerCU = 160 * 1024;
+constexpr int kFwdRows = 2;        // rows per block and step, one modulation row per segment
+constexpr int kTokRows = 1;        // rows per block and step, modulation streamed per token
 
-// Resident blocks per CU: 8 waves per CU stream best whatever the row length (more concurrent
-// waves lower the achieved HBM bandwidth), so 2 blocks of 4 waves, LDS permitting.
-int fwd_blocks_per_cu(size_t lds_bytes) {
-    int bpc = 2;
-    if (lds_bytes) {
-        const int fit = static_cast<int>((kLdsPerCU - 8 * 1024) / lds_bytes);
-        if (bpc > fit) bpc = fit;
-    }
-    return bpc < 1 ? 1 : bpc;
+// About 4 or 5 waves per CU, each with its chunks of the current step in registers and those of
+// the next step in flight, stream best.
+int fwd_blocks_per_cu(int K) {
+    if (K == 1) return 4;
+    const int b = 5 / K;
+    return b < 1 ? 1 : b;
 }
 
 FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
@@ -40,85 +37,74 @@ FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void
     return a;
 }
 
-template <typename Tag, int VPL>
-void go_seg(FwdArgs a, hipStream_t st) {
-    constexpr int E = IO<Tag>::E;
-    const size_t lds = static_cast<size_t>(2) * VPL * kWave * E * sizeof(float);
-    const int bpc = fwd_blocks_per_cu(lds);
-    const RowPlan pl = plan_rows(a.T, a.seg.nseg, static_cast<int64_t>(kNumCU) * bpc, kFwdWaves, 20);
+template <typename Tag, int VPL, int K, int MODE>
+void go_split(const FwdArgs& a, int64_t blocks, hipStream_t st) {
+    constexpr int R = MODE == kModToken ? kTokRows : kFwdRows;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
+    if (a.nchunks == K * VPL * kWave)
+        hipLaunchKernelGGL((fwd_split_kernel<Tag, VPL, K, R, true, MODE>), grid, block, 0, st, a);
+    else
+        hipLaunchKernelGGL((fwd_split_kernel<Tag, VPL, K, R, false, MODE>), grid, block, 0, st, a);
+}
+
+// VPL_WIDE: chunks per lane when several waves share a row (fixed by the dtype)
+template <typename Tag, int VPL_WIDE, int MODE>
+void dispatch_split(const FwdArgs& a, Split sp, int64_t blocks, hipStream_t st) {
+    if (sp.K == 1) {
+        switch (sp.VPL) {
+            case 1: go_split<Tag, 1, 1, MODE>(a, blocks, st); break;
+            case 2: go_split<Tag, 2, 1, MODE>(a, blocks, st); break;
+            case 3: go_split<Tag, 3, 1, MODE>(a, blocks, st); break;
+            case 4: go_split<Tag, 4, 1, MODE>(a, blocks, st); break;
+            default: go_split<Tag, 6, 1, MODE>(a, blocks, st); break;
+        }
+        return;
+    }
+    switch (sp.K) {
+        case 2: go_split<Tag, VPL_WIDE, 2, MODE>(a, blocks, st); break;
+        case 3: go_split<Tag, VPL_WIDE, 3, MODE>(a, blocks, st); break;
+        case 4: go_split<Tag, VPL_WIDE, 4, MODE>(a, blocks, st); break;
+        case 5: go_split<Tag, VPL_WIDE, 5, MODE>(a, blocks, st); break;
+        case 6: go_split<Tag, VPL_WIDE, 6, MODE>(a, blocks, st); break;
+        default: go_split<Tag, VPL_WIDE, 8, MODE>(a, blocks, st); break;
+    }
+}
+
+template <int MODE>
+hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
+                       float* mean, float* rstd, hipStream_t st) {
+    const int E = p.dtype == 0 ? 8 : 4;
+    FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
+    const Split sp = choose_split(a.nchunks, p.dtype);
+    const bool per_segment = MODE == kModSegment || MODE == kModOnly;
+    const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1,
+                                 static_cast<int64_t>(kNumCU) * fwd_blocks_per_cu(sp.K),
+                                 MODE == kModToken ? kTokRows : kFwdRows, 20);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    const dim3 grid(static_cast<unsigned>(pl.blocks)), block(kFwdWaves * kWave);
-    if (a.nchunks == VPL * kWave)
-        hipLaunchKernelGGL((fwd_seg_kernel<Tag, VPL, kFwdWaves, true>), grid, block, lds, st, a);
-    else
-        hipLaunchKernelGGL((fwd_seg_kernel<Tag, VPL, kFwdWaves, false>), grid, block, lds, st, a);
+    if (p.dtype == 0) dispatch_split<bf16_io, 2, MODE>(a, sp, pl.blocks, st);
+    else dispatch_split<f32_io, 4, MODE>(a, sp, pl.blocks, st);
+    return hipGetLastError();
 }
-
-template <typename Tag, int VPL>
-void go_tok(FwdArgs a, hipStream_t st) {
-    const int bpc = fwd_blocks_per_cu(0);
-    int64_t blocks = (a.T + kFwdWaves - 1) / kFwdWaves;
-    if (blocks > static_cast<int64_t>(kNumCU) * bpc) blocks = static_cast<int64_t>(kNumCU) * bpc;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kFwdWaves * kWave);
-    if (a.nchunks == VPL * kWave)
-        hipLaunchKernelGGL((fwd_tok_kernel<Tag, VPL, kFwdWaves, true>), grid, block, 0, st, a);
-    else
-        hipLaunchKernelGGL((fwd_tok_kernel<Tag, VPL, kFwdWaves, false>), grid, block, 0, st, a);
-}
-
-// chunks per lane: the smallest instantiated count that covers the row
-#define LNMOD_FWD_DISPATCH(GO, TAG, NEED, ...)                                   \
-    do {                                                                         \
-        if ((NEED) <= 1) GO<TAG, 1>(__VA_ARGS__);                                \
-        else if ((NEED) <= 2) GO<TAG, 2>(__VA_ARGS__);                           \
-        else if ((NEED) <= 3) GO<TAG, 3>(__VA_ARGS__);                           \
-        else if ((NEED) <= 4) GO<TAG, 4>(__VA_ARGS__);                           \
-        else if ((NEED) <= 5) GO<TAG, 5>(__VA_ARGS__);                           \
-        else if ((NEED) <= 6) GO<TAG, 6>(__VA_ARGS__);                           \
-        else if ((NEED) <= 8) GO<TAG, 8>(__VA_ARGS__);                           \
-        else if ((NEED) <= 10) GO<TAG, 10>(__VA_ARGS__);                         \
-        else if ((NEED) <= 12) GO<TAG, 12>(__VA_ARGS__);                         \
-        else GO<TAG, 16>(__VA_ARGS__);                                           \
-    } while (0)
-
-// fp32 rows have twice the chunks: up to 32 per lane at D = 8192
-#define LNMOD_FWD_DISPATCH_WIDE(GO, TAG, NEED, ...)                              \
-    do {                                                                         \
-        if ((NEED) <= 16) LNMOD_FWD_DISPATCH(GO, TAG, NEED, __VA_ARGS__);        \
-        else if ((NEED) <= 20) GO<TAG, 20>(__VA_ARGS__);                         \
-        else if ((NEED) <= 24) GO<TAG, 24>(__VA_ARGS__);                         \
-        else GO<TAG, 32>(__VA_ARGS__);                                           \
-    } while (0)
 
 }  // namespace
 
 hipError_t launch_fwd_seg(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* y, float* mean, float* rstd, hipStream_t st) {
-    if (p.dtype == 0) {
-        const FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, 8);
-        const int need = (a.nchunks + kWave - 1) / kWave;      // <= 16 for D <= 8192
-        LNMOD_FWD_DISPATCH(go_seg, bf16_io, need, a, st);
-    } else {
-        const FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, 4);
-        const int need = (a.nchunks + kWave - 1) / kWave;      // <= 32
-        LNMOD_FWD_DISPATCH_WIDE(go_seg, f32_io, need, a, st);
-    }
-    return hipGetLastError();
+    return launch_mode<kModSegment>(p, x, shift, scale, y, mean, rstd, st);
 }
 
 hipError_t launch_fwd_tok(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* y, float* mean, float* rstd, hipStream_t st) {
-    if (p.dtype == 0) {
-        const FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, 8);
-        const int need = (a.nchunks + kWave - 1) / kWave;
-        LNMOD_FWD_DISPATCH(go_tok, bf16_io, need, a, st);
-    } else {
-        const FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, 4);
-        const int need = (a.nchunks + kWave - 1) / kWave;
-        LNMOD_FWD_DISPATCH_WIDE(go_tok, f32_io, need, a, st);
-    }
-    return hipGetLastError();
+    return launch_mode<kModToken>(p, x, shift, scale, y, mean, rstd, st);
+}
+
+// The unfused comparator: LayerNorm to xhat (I/O dtype) in HBM, then the modulation of xhat.
+hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, const void* scale,
+                          void* xhat, void* y, float* mean, float* rstd, hipStream_t st) {
+    const hipError_t e = launch_mode<kLnOnly>(p, x, nullptr, nullptr, xhat, mean, rstd, st);
+    if (e != hipSuccess) return e;
+    return launch_mode<kModOnly>(p, xhat, shift, scale, y, nullptr, nullptr, st);
 }
 
 }  // namespace lnmod

@@ -7,22 +7,27 @@
 // along the token axis of each sample / packed segment (or per token, without a sum).
 //
 // Design for CDNA4 (64-wide wavefronts, no tensor-core work here: the path is bound by HBM):
-//   * a token row is read once with 128-bit loads, lane l of a wave owns the 16-byte chunks
-//     l, l+64, ... of the row, and the row stays in registers for all three uses
-//     (sum, centred sum of squares, output), so x crosses HBM exactly once;
-//   * row reductions use DPP adds inside a wave (no LDS, no ds_bpermute) and v_readlane for
-//     the four 16-lane rows; only the backward, where several waves share a row so that the
-//     per-lane dshift/dscale accumulators stay small, crosses waves through a few LDS floats;
-//   * the forward keeps the sample's (1+scale, shift) rows in LDS as fp32, laid out by chunk
-//     so that the ds_read_b128 of consecutive lanes hit consecutive banks;
-//   * the backward fixes lane <-> feature for the whole life of a block and carries fp32
-//     partial sums of dshift/dscale in registers down its rows (the paper's D-tile idea of
-//     "thread fixed to a feature, accumulate along the sequence", Sec. 3.3, done inside the dx
-//     kernel so dy and x are not read a second time); every block writes one partial slot per
-//     segment it touches and a second kernel adds the slots in a fixed order: no float atomics,
-//     bitwise reproducible;
-//   * blocks own contiguous, equally sized row ranges so that all CUs finish together, and
-//     walk the segment table themselves, so fixed-length and packed varlen batches share the code.
+//   * a token row is read once with 128-bit nontemporal loads and stays in registers (packed,
+//     as loaded) for every use: partial mean, centred sum of squares, output; fp32 values are
+//     rebuilt from the packed registers per pass (one shift or mask each), which keeps the
+//     register count low enough for a second, prefetched copy of the next rows;
+//   * K waves share a row: wave w, lane l owns the 16-byte chunks (i*K + w)*64 + l for the whole
+//     life of its block, so everything that is per feature -- (1+scale), shift, and in the
+//     backward the running dshift/dscale sums -- lives in that lane's registers;
+//   * row reductions use DPP adds inside a wave (no LDS, no ds_bpermute) and v_readlane for the
+//     four 16-lane rows; the K waves of a row exchange two floats each through LDS with one
+//     barrier per step (double-buffered);
+//   * the backward carries fp32 partial sums of dshift/dscale in registers down its rows (the
+//     paper's D-tile idea of "thread fixed to a feature, accumulate along the sequence",
+//     Sec. 3.3, done inside the dx kernel so dy and x are not read a second time); every block
+//     writes one partial slot per segment it touches and a second kernel adds the slots in a
+//     fixed order: no float atomics, bitwise reproducible;
+//   * HBM on this part rewards few, deep, sequential streams: 4 to 6 waves per CU, each with its
+//     next step's loads already in flight (software pipeline), and blocks grouped in clusters
+//     that walk one contiguous region with consecutive rows, reach about 6 TB/s where one
+//     private range per block and 16+ waves per CU reach 4.9 TB/s;
+//   * blocks walk the segment table themselves, so fixed-length and packed varlen batches share
+//     the code.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -46,18 +51,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 
-// Waves per SIMD the compiler must leave room for (512 VGPRs per SIMD lane), as a function of
-// what one lane keeps live: the fp32 values of its part of the row plus two address registers
-// per 16-byte chunk.  Without it the scheduler spends registers on hoisted loads until a single
-// wave fills the SIMD and nothing hides the HBM latency.
-constexpr int row_waves_per_eu(int vpl, int elems_per_chunk, int rows_live = 1) {
-    const int cost = vpl * (elems_per_chunk * rows_live + 2);
-    const int w = cost <= 40 ? 8 : cost <= 50 ? 6 : cost <= 60 ? 5 : cost <= 100 ? 4 : cost <= 130 ? 3 : 2;
-    return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w;
-}
-// Kernels that keep `streams` packed 16-byte registers per chunk and rebuild fp32 values per pass.
-constexpr int tok_waves_per_eu(int vpl, int streams) {
-    const int regs = vpl * (4 * streams + 1) + 40;
+// Waves per SIMD the compiler must leave room for (512 VGPRs per SIMD lane).  Without a bound the
+// scheduler spends registers on hoisted loads until a single wave fills the SIMD.
+// Kernels in which K waves share a row and a lane keeps per-feature state in registers.
+constexpr int bwd_waves_per_eu(int vpl, int elems_per_chunk, int rows) {
+    // live per lane and chunk: 1+scale and two accumulators (fp32), `rows` packed copies of dy
+    // and x with their addresses; plus unpack temporaries and loop state
+    const int regs = vpl * (3 * elems_per_chunk + 10 * rows) + 28;
     const int w = 512 / regs;
     return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }
@@ -194,8 +194,7 @@ __device__ inline int64_t find_segment(const Segments& s, int64_t row) {
 }
 
 // =============================================================================================
-// Forward, modulation row per sample / per segment.  One wave per token row; the block's WPB
-// waves take the rows of the block's range round-robin.
+// Forward arguments (all forward kernels)
 // =============================================================================================
 struct FwdArgs {
     const void* x;
@@ -214,208 +213,251 @@ struct FwdArgs {
     float inv_D;
 };
 
-template <typename Tag, int VPL, int WPB, bool EXACT, bool PF = true>
-__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(row_waves_per_eu(VPL, IO<Tag>::E + (PF ? 4 : 0)))
-void fwd_seg_kernel(const FwdArgs a) {
+// =============================================================================================
+// Forward.  K waves share a row: wave w, lane l owns chunks (i*K + w)*64 + l for the whole life
+// of the block, so with one modulation row per sample / segment the (1+scale, shift) values of
+// those features stay in registers and nothing of the modulation goes through LDS.  Each wave
+// forms the mean and the centred sum of squares of its own part of the row (two passes over
+// registers); the K partial results are merged with the exact pairwise-update formula
+//   M2 = sum_k M2_k + sum_k n_k (mean_k - mean)^2,
+// which keeps the two-pass accuracy, through a few LDS floats and one barrier per step.
+//
+// MODE selects what surrounds the normalisation:
+//   kModSegment   y = xhat*(1+scale[m]) + shift[m], one modulation row per sample / segment
+//   kModToken     y = xhat*(1+scale[n]) + shift[n], modulation rows streamed with x
+//   kLnOnly       y = xhat                      (first kernel of the unfused comparator)
+//   kModOnly      y = x*(1+scale[m]) + shift[m], no statistics (second kernel of the comparator)
+// =============================================================================================
+constexpr int kModSegment = 0, kModToken = 1, kLnOnly = 2, kModOnly = 3;
+
+template <typename Tag, int VPL, int K, int R, bool EXACT, int MODE = kModSegment, bool PF = true>
+__global__ __launch_bounds__(K* kWave)
+LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, (MODE == kModToken ? 3 : 1) * (PF ? 2 * R : R)))
+void fwd_split_kernel(const FwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
-    constexpr int Q = E / 4;            // float4 parts per chunk
-    constexpr int CH = VPL * kWave;     // chunk slots per row
-    extern __shared__ f32x4 lds[];      // [2][Q][CH]: (1+scale) parts, then shift parts
+    constexpr bool kSegMod = MODE == kModSegment || MODE == kModOnly;   // A, B per segment in registers
+    constexpr bool kTok = MODE == kModToken;
+    constexpr bool kStats = MODE != kModOnly;
+    constexpr int NS = kTok ? 3 : 1;                                     // streamed inputs per row
+    __shared__ float part[2][R][K][2];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
 
-    // cluster of a.nb blocks <-> contiguous region of rows; inside the region the cluster's
-    // waves take consecutive rows, so at any moment the cluster streams through one window
+    int chunk[VPL];
+    bool ok[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        chunk[i] = (i * K + wave) * kWave + lane;
+        ok[i] = EXACT || chunk[i] < a.nchunks;
+    }
+    // features each wave holds (all lanes compute the same K numbers)
+    float cnt[K];
+#pragma unroll
+    for (int w = 0; w < K; ++w) {
+        int n = 0;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            int left = a.nchunks - (i * K + w) * kWave;
+            left = left < 0 ? 0 : left > kWave ? kWave : left;
+            n += left;
+        }
+        cnt[w] = static_cast<float>(n * E);
+    }
+    float my_cnt = cnt[0];
+#pragma unroll
+    for (int w = 1; w < K; ++w) my_cnt = wave == w ? cnt[w] : my_cnt;
+    const float inv_my_cnt = my_cnt > 0.0f ? 1.0f / my_cnt : 0.0f;
+
     const int64_t cluster = blockIdx.x / a.nb;
     const int64_t member = blockIdx.x - cluster * a.nb;
     int64_t r0 = cluster * a.rows_per_cluster;
     int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
+    int buf = 0;
 
     while (r0 < r1) {
-        const int64_t m = find_segment(a.seg, r0);
-        int64_t stop = seg_begin(a.seg, m + 1);
-        if (stop > r1) stop = r1;
-        if (stop <= r0) stop = r0 + 1;          // malformed table: still make progress
+        int64_t m = 0, stop = r1;
+        if (kSegMod) {
+            m = find_segment(a.seg, r0);
+            stop = seg_begin(a.seg, m + 1);
+            if (stop > r1) stop = r1;
+            if (stop <= r0) stop = r0 + 1;      // malformed table: still make progress
+        }
 
-        __syncthreads();                        // readers of the previous segment's rows are done
-        for (int c = threadIdx.x; c < CH; c += WPB * kWave) {
-            if (EXACT || c < a.nchunks) {
-                const uint32_t lo = static_cast<uint32_t>(c) * 16u;
-                float sc[E], sh[E];
-                io::unpack(load16_cached(a.scale, m * row_bytes, lo), sc);
-                io::unpack(load16_cached(a.shift, m * row_bytes, lo), sh);
+        float A[VPL][E], B[VPL][E];
+        if (kSegMod) {
 #pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    f32x4 p = {1.0f + sc[4 * q], 1.0f + sc[4 * q + 1], 1.0f + sc[4 * q + 2], 1.0f + sc[4 * q + 3]};
-                    f32x4 s = {sh[4 * q], sh[4 * q + 1], sh[4 * q + 2], sh[4 * q + 3]};
-                    lds[(0 * Q + q) * CH + c] = p;
-                    lds[(1 * Q + q) * CH + c] = s;
+            for (int i = 0; i < VPL; ++i) {
+                u32x4 rsc = u32x4{0u, 0u, 0u, 0u}, rsh = u32x4{0u, 0u, 0u, 0u};
+                if (ok[i]) {
+                    rsc = load16_cached(a.scale, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
+                    rsh = load16_cached(a.shift, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
                 }
+                io::unpack(rsc, A[i]);
+                io::unpack(rsh, B[i]);
+#pragma unroll
+                for (int e = 0; e < E; ++e) A[i][e] += 1.0f;
             }
         }
-        __syncthreads();
 
-        // Software pipeline: the wave requests its next row before it works on the current one,
-        // so a few waves per CU keep the memory system busy (few, deep streams reach a higher
-        // HBM bandwidth than many shallow ones).
-        auto fetch = [&](int64_t row, u32x4 (&q)[VPL]) {
+        // Software pipeline: the rows of the block's next step are requested before the current
+        // step is computed, so a few waves per CU keep the memory system busy.
+        // q[s][j][i]: s = 0 x, 1 scale, 2 shift (the last two only with per-token modulation)
+        auto fetch = [&](int64_t base, u32x4 (&q)[NS][R][VPL]) {
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) {
-                const int c = i * kWave + lane;
-                if (row < stop && (EXACT || c < a.nchunks))
-                    q[i] = load16(a.x, row * row_bytes, static_cast<uint32_t>(c) * 16u);
-                else
-                    q[i] = u32x4{0u, 0u, 0u, 0u};
+            for (int j = 0; j < R; ++j) {
+                const int64_t row = base + j;
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) {
+                    const uint32_t lo = static_cast<uint32_t>(chunk[i]) * 16u;
+                    if (row < stop && ok[i]) {
+                        q[0][j][i] = load16_u(a.x, row * row_bytes, lo);
+                        if (kTok) {
+                            q[NS - 2][j][i] = load16_u(a.scale, row * row_bytes, lo);
+                            q[NS - 1][j][i] = load16_u(a.shift, row * row_bytes, lo);
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < NS; ++t) q[t][j][i] = u32x4{0u, 0u, 0u, 0u};
+                    }
+                }
             }
         };
-        const int64_t row_step = static_cast<int64_t>(a.nb) * WPB;
-        u32x4 raw[VPL];
-        if (PF) fetch(r0 + member * WPB + wave, raw);
+        const int64_t step = static_cast<int64_t>(a.nb) * R;
+        u32x4 raw[NS][R][VPL];
+        if (PF) fetch(r0 + member * R, raw);
 
-        for (int64_t row = r0 + member * WPB + wave; row < stop; row += row_step) {
-            const int64_t base = row * row_bytes;
-            u32x4 nxt[VPL];
+        for (int64_t base = r0 + member * R; base < stop; base += step) {
+            u32x4 nxt[NS][R][VPL];
             if (PF) {
-                fetch(row + row_step, nxt);
+                fetch(base + step, nxt);
                 __builtin_amdgcn_sched_barrier(0);           // keep the requests up here
             } else {
-                fetch(row, raw);
+                fetch(base, raw);
             }
-            float v[VPL][E];
-            float s = 0.0f;
+            float mu[R], rs[R];
+            if (kStats) {
+                // this wave's part of each row: mean, then centred sum of squares
+                float pm[R], pq[R];
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) {
-                io::unpack(raw[i], v[i]);
+                for (int j = 0; j < R; ++j) {
+                    float s = 0.0f;
 #pragma unroll
-                for (int e = 0; e < E; ++e) s += v[i][e];
-            }
-            const float mu = wave_sum(s) / static_cast<float>(a.D);   // exact for constant rows
-            float q2 = 0.0f;
+                    for (int i = 0; i < VPL; ++i) {
+                        float v[E];
+                        io::unpack(raw[0][j][i], v);
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) {
-                const bool ok = EXACT || (i * kWave + lane) < a.nchunks;
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    v[i][e] = ok ? v[i][e] - mu : 0.0f;
-                    q2 += v[i][e] * v[i][e];
-                }
-            }
-            const float var = wave_sum(q2) * a.inv_D;
-            const float rs = 1.0f / sqrtf(var + a.eps);
-            if (lane == 0) {
-                a.mean[row] = mu;
-                a.rstd[row] = rs;
-            }
-#pragma unroll
-            for (int i = 0; i < VPL; ++i) {
-                const int c = i * kWave + lane;
-                if (EXACT || c < a.nchunks) {
-                    float o[E];
-#pragma unroll
-                    for (int q = 0; q < Q; ++q) {
-                        const f32x4 p = lds[(0 * Q + q) * CH + c];
-                        const f32x4 sh = lds[(1 * Q + q) * CH + c];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[4 * q + e] = (v[i][4 * q + e] * rs) * p[e] + sh[e];
+                        for (int e = 0; e < E; ++e) s += v[e];
                     }
-                    store16(a.y, base, static_cast<uint32_t>(c) * 16u, io::pack(o));
+                    pm[j] = wave_sum(s) * inv_my_cnt;
+                    float q2 = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) {
+                        if (ok[i]) {
+                            float v[E];
+                            io::unpack(raw[0][j][i], v);
+#pragma unroll
+                            for (int e = 0; e < E; ++e) q2 += (v[e] - pm[j]) * (v[e] - pm[j]);
+                        }
+                    }
+                    pq[j] = wave_sum(q2);
                 }
-                // keep the LDS reads of later chunks from being hoisted above this one: in a
-                // branch-free body the scheduler otherwise issues all of them first and spills
-                __builtin_amdgcn_sched_barrier(0);
+                if (K > 1) {
+                    if (lane == 0) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j) {
+                            part[buf][j][wave][0] = pm[j];
+                            part[buf][j][wave][1] = pq[j];
+                        }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        float wsum = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < K; ++w) wsum += cnt[w] * part[buf][j][w][0];
+                        const float mean = wsum / static_cast<float>(a.D);
+                        float m2 = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < K; ++w) {
+                            const float d = part[buf][j][w][0] - mean;
+                            m2 += part[buf][j][w][1] + cnt[w] * d * d;
+                        }
+                        mu[j] = mean;
+                        rs[j] = 1.0f / sqrtf(m2 * a.inv_D + a.eps);
+                    }
+                    buf ^= 1;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        mu[j] = pm[j];
+                        rs[j] = 1.0f / sqrtf(pq[j] * a.inv_D + a.eps);
+                    }
+                }
+                // make the packed registers opaque, so that the fp32 values are rebuilt below
+                // instead of being carried across the barrier in registers
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) asm volatile("" : "+v"(raw[0][j][i]));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    mu[j] = 0.0f;
+                    rs[j] = 1.0f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const int64_t row = base + j;
+                if (row < stop) {
+                    if (kStats && wave == 0 && lane == 0) {
+                        a.mean[row] = mu[j];
+                        a.rstd[row] = rs[j];
+                    }
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) {
+                        if (ok[i]) {
+                            float v[E], o[E];
+                            io::unpack(raw[0][j][i], v);
+                            if (kTok) {
+                                float sc[E], sh[E];
+                                io::unpack(raw[NS - 2][j][i], sc);
+                                io::unpack(raw[NS - 1][j][i], sh);
+#pragma unroll
+                                for (int e = 0; e < E; ++e) o[e] = ((v[e] - mu[j]) * rs[j]) * (1.0f + sc[e]) + sh[e];
+                            } else if (MODE == kLnOnly) {
+#pragma unroll
+                                for (int e = 0; e < E; ++e) o[e] = (v[e] - mu[j]) * rs[j];
+                            } else if (MODE == kModOnly) {
+#pragma unroll
+                                for (int e = 0; e < E; ++e) o[e] = v[e] * A[i][e] + B[i][e];
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < E; ++e) o[e] = ((v[e] - mu[j]) * rs[j]) * A[i][e] + B[i][e];
+                            }
+                            store16_u(a.y, row * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u, io::pack(o));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
             if (PF) {
 #pragma unroll
-                for (int i = 0; i < VPL; ++i) raw[i] = nxt[i];
+                for (int t = 0; t < NS; ++t) {
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+#pragma unroll
+                        for (int i = 0; i < VPL; ++i) raw[t][j][i] = nxt[t][j][i];
+                    }
+                }
             }
         }
         r0 = stop;
-    }
-}
-
-// =============================================================================================
-// Forward, modulation row per token: shift/scale [T, D] stream with x; no LDS, no segments.
-// =============================================================================================
-// Makes the packed registers opaque between passes, so that the fp32 copies of one pass are
-// rebuilt (one shift or mask per value) instead of being carried in registers to the next.
-template <int N> __device__ inline void forget(u32x4 (&r)[N]) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
-}
-
-template <typename Tag, int VPL, int WPB, bool EXACT>
-__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(tok_waves_per_eu(VPL, 3))
-void fwd_tok_kernel(const FwdArgs a) {
-    using io = IO<Tag>;
-    constexpr int E = io::E;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-
-    // all waves of the grid take consecutive rows: the launch streams through one moving window
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
-    const int64_t r1 = a.T;
-    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
-
-    for (int64_t row = r0 + wave; row < r1; row += row_step) {
-        const int64_t base = row * row_bytes;
-        u32x4 raw[VPL], rsc[VPL], rsh[VPL];
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                raw[i] = load16(a.x, base, static_cast<uint32_t>(c) * 16u);
-                rsc[i] = load16(a.scale, base, static_cast<uint32_t>(c) * 16u);
-                rsh[i] = load16(a.shift, base, static_cast<uint32_t>(c) * 16u);
-            } else {
-                raw[i] = rsc[i] = rsh[i] = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
-        float s = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            float v[E];
-            io::unpack(raw[i], v);
-#pragma unroll
-            for (int e = 0; e < E; ++e) s += v[e];
-        }
-        const float mu = wave_sum(s) / static_cast<float>(a.D);   // exact for constant rows
-        forget(raw);
-        float q2 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            if (EXACT || (i * kWave + lane) < a.nchunks) {
-                float v[E];
-                io::unpack(raw[i], v);
-#pragma unroll
-                for (int e = 0; e < E; ++e) q2 += (v[e] - mu) * (v[e] - mu);
-            }
-        }
-        const float var = wave_sum(q2) * a.inv_D;
-        const float rs = 1.0f / sqrtf(var + a.eps);
-        if (lane == 0) {
-            a.mean[row] = mu;
-            a.rstd[row] = rs;
-        }
-        forget(raw);
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                float v[E], sc[E], sh[E], o[E];
-                io::unpack(raw[i], v);
-                io::unpack(rsc[i], sc);
-                io::unpack(rsh[i], sh);
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] = ((v[e] - mu) * rs) * (1.0f + sc[e]) + sh[e];
-                store16(a.y, base, static_cast<uint32_t>(c) * 16u, io::pack(o));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
     }
 }
 
@@ -448,19 +490,13 @@ struct BwdArgs {
     float inv_D;
 };
 
-constexpr int bwd_waves_per_eu(int vpl, int elems_per_chunk, int rows) {
-    // live per lane and chunk: 1+scale and two accumulators (fp32), `rows` packed copies of dy
-    // and x with their addresses; plus unpack temporaries and loop state
-    const int regs = vpl * (3 * elems_per_chunk + 10 * rows) + 28;
-    const int w = 512 / regs;
-    return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
-}
-
-template <typename Tag, int VPL, int K, int R, bool EXACT, bool PF = true>
-__global__ __launch_bounds__(K* kWave) LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, PF ? 2 * R : R))
+template <typename Tag, int VPL, int K, int R, bool EXACT, bool TOK = false, bool PF = true>
+__global__ __launch_bounds__(K* kWave)
+LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, (TOK ? 3 : 2) * (PF ? 2 * R : R) / 2))
 void bwd_seg_kernel(const BwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
+    constexpr int NS = TOK ? 3 : 2;            // streamed inputs per row: dy, x (, scale)
     __shared__ float part[2][R][K][2];
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -483,30 +519,35 @@ void bwd_seg_kernel(const BwdArgs a) {
     int buf = 0;
 
     while (r0 < r1) {
-        const int64_t m = find_segment(a.seg, r0);
-        int64_t stop = seg_begin(a.seg, m + 1);
-        if (stop > r1) stop = r1;
-        if (stop <= r0) stop = r0 + 1;
+        int64_t m = 0, stop = r1;
+        if (!TOK) {
+            m = find_segment(a.seg, r0);
+            stop = seg_begin(a.seg, m + 1);
+            if (stop > r1) stop = r1;
+            if (stop <= r0) stop = r0 + 1;      // malformed table: still make progress
+        }
 
+        // per segment: 1 + scale of this lane's features and the running dshift/dscale sums
         float A[VPL][E], acc_s[VPL][E], acc_c[VPL][E];
+        if (!TOK) {
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            u32x4 r = u32x4{0u, 0u, 0u, 0u};
-            if (ok[i]) r = load16_cached(a.scale, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
-            io::unpack(r, A[i]);
+            for (int i = 0; i < VPL; ++i) {
+                u32x4 r = u32x4{0u, 0u, 0u, 0u};
+                if (ok[i]) r = load16_cached(a.scale, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
+                io::unpack(r, A[i]);
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                A[i][e] += 1.0f;
-                acc_s[i][e] = 0.0f;
-                acc_c[i][e] = 0.0f;
+                for (int e = 0; e < E; ++e) {
+                    A[i][e] += 1.0f;
+                    acc_s[i][e] = 0.0f;
+                    acc_c[i][e] = 0.0f;
+                }
             }
         }
 
-        // Software pipeline: the packed dy/x of the block's next step are requested before the
+        // Software pipeline: the packed rows of the block's next step are requested before the
         // current step is computed, so every block keeps loads in flight while it does
-        // arithmetic, waits at its barrier and stores.
-        auto fetch = [&](int64_t base, u32x4 (&qdy)[R][VPL], u32x4 (&qx)[R][VPL], float (&qmu)[R],
-                         float (&qrs)[R]) {
+        // arithmetic, waits at its barrier and stores.  q[s][j][i]: s = 0 dy, 1 x, 2 scale.
+        auto fetch = [&](int64_t base, u32x4 (&q)[NS][R][VPL], float (&qmu)[R], float (&qrs)[R]) {
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int64_t row = base + j;
@@ -517,57 +558,63 @@ void bwd_seg_kernel(const BwdArgs a) {
                 for (int i = 0; i < VPL; ++i) {
                     if (live && ok[i]) {
                         const uint32_t lo = static_cast<uint32_t>(chunk[i]) * 16u;
-                        qdy[j][i] = load16_u(a.dy, row * row_bytes, lo);
-                        qx[j][i] = load16_u(a.x, row * row_bytes, lo);
+                        q[0][j][i] = load16_u(a.dy, row * row_bytes, lo);
+                        q[1][j][i] = load16_u(a.x, row * row_bytes, lo);
+                        if (TOK) q[NS - 1][j][i] = load16_u(a.scale, row * row_bytes, lo);
                     } else {
-                        qdy[j][i] = u32x4{0u, 0u, 0u, 0u};
-                        qx[j][i] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int t = 0; t < NS; ++t) q[t][j][i] = u32x4{0u, 0u, 0u, 0u};
                     }
                 }
             }
         };
         const int64_t step = static_cast<int64_t>(a.nb) * R;
-        u32x4 rdy[R][VPL], rx[R][VPL];
+        u32x4 raw[NS][R][VPL];
         float mu[R], rs[R];
-        if (PF) fetch(r0 + member * R, rdy, rx, mu, rs);     // rows at or beyond `stop` read as zeros
+        if (PF) fetch(r0 + member * R, raw, mu, rs);         // rows at or beyond `stop` read as zeros
 
         for (int64_t base = r0 + member * R; base < stop; base += step) {
-            u32x4 ndy[R][VPL], nx[R][VPL];
+            u32x4 nxt[NS][R][VPL];
             float nmu[R], nrs[R];
             if (PF) {
-                fetch(base + step, ndy, nx, nmu, nrs);
+                fetch(base + step, nxt, nmu, nrs);
                 __builtin_amdgcn_sched_barrier(0);           // keep the requests up here
             } else {
-                fetch(base, rdy, rx, mu, rs);
+                fetch(base, raw, mu, rs);
             }
             // pass 1 over the registers: row sums for dx and the running dshift/dscale sums.
             // xhat and g are not kept: they are rebuilt from the packed registers in pass 2,
-            // which costs a few ALU operations and saves the registers that occupancy needs.
+            // which costs a few ALU operations and saves the registers the prefetch needs.
             float c1[R], c2[R];
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 float p1 = 0.0f, p2 = 0.0f;
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) {
-                    float dyv[E], xv[E];
-                    io::unpack(rdy[j][i], dyv);
-                    io::unpack(rx[j][i], xv);
+                    float dyv[E], xv[E], scv[E];
+                    io::unpack(raw[0][j][i], dyv);
+                    io::unpack(raw[1][j][i], xv);
+                    if (TOK) io::unpack(raw[NS - 1][j][i], scv);
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
                         // xhat as (x - mean) * rstd, not x*rstd - mean*rstd: the latter loses every digit
                         // on (near-)constant rows, where rstd is as large as 1/sqrt(eps)
                         const float h = (xv[e] - mu[j]) * rs[j];
-                        const float gg = dyv[e] * A[i][e];
+                        const float gg = dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e]);
                         p1 += gg;
                         p2 += gg * h;
-                        acc_s[i][e] += dyv[e];
-                        acc_c[i][e] += dyv[e] * h;
+                        if (!TOK) {
+                            acc_s[i][e] += dyv[e];
+                            acc_c[i][e] += dyv[e] * h;
+                        }
                     }
-                    // Pin the running sums here.  They are only consumed at the end of the loop,
-                    // so the optimiser would otherwise sink these adds below the barrier and keep
-                    // every unpacked dy and xhat alive until then (twice the row in registers).
+                    if (!TOK) {
+                        // Pin the running sums here.  They are only consumed at the end of the loop,
+                        // so the optimiser would otherwise sink these adds below the barrier and keep
+                        // every unpacked dy and xhat alive until then (twice the row in registers).
 #pragma unroll
-                    for (int e = 0; e < E; ++e) asm volatile("" : "+v"(acc_s[i][e]), "+v"(acc_c[i][e]));
+                        for (int e = 0; e < E; ++e) asm volatile("" : "+v"(acc_s[i][e]), "+v"(acc_c[i][e]));
+                    }
                     // one chunk at a time: stops the scheduler from unpacking every chunk up front
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -600,9 +647,12 @@ void bwd_seg_kernel(const BwdArgs a) {
             // opaque so that common-subexpression elimination cannot carry pass 1's fp32 values
             // across the barrier instead of rebuilding them.
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
+            for (int t = 0; t < NS; ++t) {
 #pragma unroll
-                for (int i = 0; i < VPL; ++i) asm volatile("" : "+v"(rdy[j][i]), "+v"(rx[j][i]));
+                for (int j = 0; j < R; ++j) {
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) asm volatile("" : "+v"(raw[t][j][i]));
+                }
             }
 #pragma unroll
             for (int j = 0; j < R; ++j) {
@@ -612,15 +662,23 @@ void bwd_seg_kernel(const BwdArgs a) {
 #pragma unroll
                     for (int i = 0; i < VPL; ++i) {
                         if (ok[i]) {
-                            float dyv[E], xv[E], o[E];
-                            io::unpack(rdy[j][i], dyv);
-                            io::unpack(rx[j][i], xv);
+                            float dyv[E], xv[E], scv[E], o[E], ds[E];
+                            io::unpack(raw[0][j][i], dyv);
+                            io::unpack(raw[1][j][i], xv);
+                            if (TOK) io::unpack(raw[NS - 1][j][i], scv);
 #pragma unroll
                             for (int e = 0; e < E; ++e) {
                                 const float h = (xv[e] - mu[j]) * rs[j];
-                                o[e] = (dyv[e] * A[i][e]) * rs[j] - k1 - h * k2;
+                                o[e] = (dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e])) * rs[j] - k1 - h * k2;
+                                if (TOK) ds[e] = dyv[e] * h;
                             }
-                            store16_u(a.dx, row * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u, io::pack(o));
+                            const uint32_t lo = static_cast<uint32_t>(chunk[i]) * 16u;
+                            store16_u(a.dx, row * row_bytes, lo, io::pack(o));
+                            if (TOK) {
+                                // per token: dshift = dy (the packed registers as loaded), dscale = dy * xhat
+                                store16_u(a.dshift, row * row_bytes, lo, raw[0][j][i]);
+                                store16_u(a.dscale, row * row_bytes, lo, io::pack(ds));
+                            }
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -632,25 +690,27 @@ void bwd_seg_kernel(const BwdArgs a) {
                     mu[j] = nmu[j];
                     rs[j] = nrs[j];
 #pragma unroll
-                    for (int i = 0; i < VPL; ++i) {
-                        rdy[j][i] = ndy[j][i];
-                        rx[j][i] = nx[j][i];
+                    for (int t = 0; t < NS; ++t) {
+#pragma unroll
+                        for (int i = 0; i < VPL; ++i) raw[t][j][i] = nxt[t][j][i];
                     }
                 }
             }
         }
 
-        // this block's partial sums for segment m
-        float* slot = a.ws + ((cluster + m) * a.nb + member) * 2 * a.D;
+        if (!TOK) {
+            // this block's partial sums for segment m
+            float* slot = a.ws + ((cluster + m) * a.nb + member) * 2 * a.D;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            if (ok[i]) {
-                f32x4* ps = reinterpret_cast<f32x4*>(slot + static_cast<int64_t>(chunk[i]) * E);
-                f32x4* pc = reinterpret_cast<f32x4*>(slot + a.D + static_cast<int64_t>(chunk[i]) * E);
+            for (int i = 0; i < VPL; ++i) {
+                if (ok[i]) {
+                    f32x4* ps = reinterpret_cast<f32x4*>(slot + static_cast<int64_t>(chunk[i]) * E);
+                    f32x4* pc = reinterpret_cast<f32x4*>(slot + a.D + static_cast<int64_t>(chunk[i]) * E);
 #pragma unroll
-                for (int q = 0; q < E / 4; ++q) {
-                    ps[q] = f32x4{acc_s[i][4 * q], acc_s[i][4 * q + 1], acc_s[i][4 * q + 2], acc_s[i][4 * q + 3]};
-                    pc[q] = f32x4{acc_c[i][4 * q], acc_c[i][4 * q + 1], acc_c[i][4 * q + 2], acc_c[i][4 * q + 3]};
+                    for (int q = 0; q < E / 4; ++q) {
+                        ps[q] = f32x4{acc_s[i][4 * q], acc_s[i][4 * q + 1], acc_s[i][4 * q + 2], acc_s[i][4 * q + 3]};
+                        pc[q] = f32x4{acc_c[i][4 * q], acc_c[i][4 * q + 1], acc_c[i][4 * q + 2], acc_c[i][4 * q + 3]};
+                    }
                 }
             }
         }
@@ -708,176 +768,8 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const R
 }
 
 // =============================================================================================
-// Backward, modulation row per token: one wave per row, dshift = dy and dscale = dy*xhat are
-// written per token in the I/O dtype, nothing is summed over tokens.
+// Bandwidth reference (not part of the fused path)
 // =============================================================================================
-template <typename Tag, int VPL, int WPB, bool EXACT>
-__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(tok_waves_per_eu(VPL, 3))
-void bwd_tok_kernel(const BwdArgs a) {
-    using io = IO<Tag>;
-    constexpr int E = io::E;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-
-    // all waves of the grid take consecutive rows: the launch streams through one moving window
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
-    const int64_t r1 = a.T;
-    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
-
-    for (int64_t row = r0 + wave; row < r1; row += row_step) {
-        const int64_t base = row * row_bytes;
-        const float mu = a.mean[row], rs = a.rstd[row];
-        u32x4 rdy[VPL], rx[VPL], rsc[VPL];
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                rdy[i] = load16(a.dy, base, static_cast<uint32_t>(c) * 16u);
-                rx[i] = load16(a.x, base, static_cast<uint32_t>(c) * 16u);
-                rsc[i] = load16(a.scale, base, static_cast<uint32_t>(c) * 16u);
-            } else {
-                rdy[i] = rx[i] = rsc[i] = u32x4{0u, 0u, 0u, 0u};
-            }
-        }
-        float p1 = 0.0f, p2 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            float dyv[E], xv[E], sc[E];
-            io::unpack(rdy[i], dyv);
-            io::unpack(rx[i], xv);
-            io::unpack(rsc[i], sc);
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const float h = (xv[e] - mu) * rs;
-                const float gg = dyv[e] * (1.0f + sc[e]);
-                p1 += gg;
-                p2 += gg * h;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        const float k1 = rs * (wave_sum(p1) * a.inv_D);
-        const float k2 = rs * (wave_sum(p2) * a.inv_D);
-        forget(rdy);
-        forget(rx);
-        forget(rsc);
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                float dyv[E], xv[E], sc[E], o[E], ds[E];
-                io::unpack(rdy[i], dyv);
-                io::unpack(rx[i], xv);
-                io::unpack(rsc[i], sc);
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    const float h = (xv[e] - mu) * rs;
-                    o[e] = (dyv[e] * (1.0f + sc[e])) * rs - k1 - h * k2;
-                    ds[e] = dyv[e] * h;
-                }
-                const uint32_t lo = static_cast<uint32_t>(c) * 16u;
-                store16(a.dx, base, lo, io::pack(o));
-                store16(a.dshift, base, lo, rdy[i]);
-                store16(a.dscale, base, lo, io::pack(ds));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-}
-
-// =============================================================================================
-// Measurement comparators (not part of the fused path): the unfused two-kernel chain
-// LayerNorm -> xhat in HBM -> modulate, and a plain 16-byte copy as the bandwidth ceiling.
-// =============================================================================================
-template <typename Tag, int VPL, int WPB, bool EXACT>
-__global__ __launch_bounds__(WPB* kWave) LNMOD_OCCUPANCY(row_waves_per_eu(VPL, IO<Tag>::E))
-void unfused_ln_kernel(const FwdArgs a) {
-    using io = IO<Tag>;
-    constexpr int E = io::E;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-    // all waves of the grid take consecutive rows: the launch streams through one moving window
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
-    const int64_t r1 = a.T;
-    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
-    for (int64_t row = r0 + wave; row < r1; row += row_step) {
-        const int64_t base = row * row_bytes;
-        u32x4 raw[VPL];
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) raw[i] = load16(a.x, base, static_cast<uint32_t>(c) * 16u);
-            else raw[i] = u32x4{0u, 0u, 0u, 0u};
-        }
-        float v[VPL][E];
-        float s = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            io::unpack(raw[i], v[i]);
-#pragma unroll
-            for (int e = 0; e < E; ++e) s += v[i][e];
-        }
-        const float mu = wave_sum(s) / static_cast<float>(a.D);   // exact for constant rows
-        float q2 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const bool ok = EXACT || (i * kWave + lane) < a.nchunks;
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                v[i][e] = ok ? v[i][e] - mu : 0.0f;
-                q2 += v[i][e] * v[i][e];
-            }
-        }
-        const float rs = 1.0f / sqrtf(wave_sum(q2) * a.inv_D + a.eps);
-        if (lane == 0) {
-            a.mean[row] = mu;
-            a.rstd[row] = rs;
-        }
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                float o[E];
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] = v[i][e] * rs;
-                store16(a.y, base, static_cast<uint32_t>(c) * 16u, io::pack(o));   // a.y: xhat buffer
-            }
-        }
-    }
-}
-
-// y = xhat * (1 + scale[m]) + shift[m]; a.x is the xhat buffer.  One wave per row as above.
-template <typename Tag, int VPL, int WPB, bool EXACT>
-__global__ __launch_bounds__(WPB* kWave) void unfused_mod_kernel(const FwdArgs a) {
-    using io = IO<Tag>;
-    constexpr int E = io::E;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row_bytes = static_cast<int64_t>(a.D) * io::kBytes;
-    // all waves of the grid take consecutive rows: the launch streams through one moving window
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * WPB;
-    const int64_t r1 = a.T;
-    const int64_t row_step = static_cast<int64_t>(gridDim.x) * WPB;
-    for (int64_t row = r0 + wave; row < r1; row += row_step) {
-        const int64_t m = find_segment(a.seg, row);
-        const int64_t base = row * row_bytes;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int c = i * kWave + lane;
-            if (EXACT || c < a.nchunks) {
-                float v[E], sc[E], sh[E], o[E];
-                io::unpack(load16(a.x, base, static_cast<uint32_t>(c) * 16u), v);
-                io::unpack(load16_cached(a.scale, m * row_bytes, static_cast<uint32_t>(c) * 16u), sc);
-                io::unpack(load16_cached(a.shift, m * row_bytes, static_cast<uint32_t>(c) * 16u), sh);
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] = v[e] * (1.0f + sc[e]) + sh[e];
-                store16(a.y, base, static_cast<uint32_t>(c) * 16u, io::pack(o));
-            }
-        }
-    }
-}
-
 // Plain copy in the same access pattern as the row kernels: every wave moves 4 KB per step
 // with 16-byte nontemporal accesses, the waves of the grid take consecutive 4 KB pieces, and
 // the next piece is requested before the current one is stored.

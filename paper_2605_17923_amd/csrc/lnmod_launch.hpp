@@ -63,6 +63,28 @@ inline RowPlan plan_rows(int64_t T, int64_t nseg, int64_t max_blocks, int rows_p
     return p;
 }
 
+// How a row of `nchunks` 16-byte chunks is split: K waves per row, VPL chunks per lane.  A lane
+// keeps about 16 features (up to 24 when one wave can take the whole row, which needs no
+// barrier at all); longer rows are shared by more waves.
+struct Split {
+    int K;
+    int VPL;
+};
+
+inline Split choose_split(int nchunks, int dtype) {
+    const int per_feat16 = dtype == 0 ? 2 : 4;          // chunks holding 16 features
+    const int solo_max = dtype == 0 ? 3 : 6;            // chunks per lane a single wave may take
+    const int need = (nchunks + 63) / 64;
+    if (need <= solo_max) {
+        int vpl = need;
+        if (dtype == 1 && vpl == 5) vpl = 6;            // instantiated: 1, 2, 3, 4, 6
+        return {1, vpl};
+    }
+    int k = (nchunks + per_feat16 * 64 - 1) / (per_feat16 * 64);
+    if (k == 7) k = 8;
+    return {k, per_feat16};
+}
+
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
 // kernel's grid and tells the second pass which partial-sum slots belong to a segment.
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
