@@ -26,9 +26,11 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
-# same counters' reading for lnmod_copy of known size; see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"forward": None, "backward": None}
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE), each scaled
+# by the same counter's reading for lnmod_copy of known size (FETCH_SIZE reads half the loaded
+# bytes, WRITE_SIZE the stored bytes); the runs and readings are in
+# profiles/wan14b_fwd_bwd_pmc_hbm_traffic.md.  Backward = main kernel + second pass.
+MEASURED_TRAFFIC_BYTES = {"forward": 1550948385, "backward": 2348841267}
 
 
 def algorithmic_bytes(T, D, elem):
@@ -82,6 +84,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-sample-tokens", type=int, default=75600)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run lnmod_copy on a buffer of the workload's size (a kernel of known "
+                         "traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the copy ceiling, the unfused comparison and the D=1536 forward")
     args = ap.parse_args()
@@ -99,6 +104,15 @@ def main():
     torch.cuda.set_device(0)
     B, S, D = 1, 75600, 5120
     T = B * S
+    if args.calibrate_copy:
+        src = torch.zeros(T, D, dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        stream = torch.cuda.current_stream()
+        nbytes = src.numel() * 2
+        ms = _time_ms(torch, stream, lambda: lnmod.lnmod_copy(src, dst, nbytes, stream.cuda_stream), iters=args.steps)
+        print(json.dumps({"kernel": "copy16_kernel", "bytes_read": nbytes, "bytes_written": nbytes,
+                          "avg_launch_us": round(ms * 1e3, 2), "GBs": _gbs(2 * nbytes, ms)}))
+        return
     x, dy, shift, scale = make_device_inputs(T, D, 1003, dev)
     y, dx = torch.empty_like(x), torch.empty_like(x)
     mean = torch.empty(T, dtype=torch.float32, device=dev)
