@@ -95,9 +95,10 @@ int lnmod_oracle_forward(const void *x, const void *shift, const void *scale, in
 {
     if (!cu || nseg < 0 || D <= 0) return 1;
     if (mod != LNMOD_ORACLE_PER_SEGMENT && mod != LNMOD_ORACLE_PER_TOKEN) return 1;
+    for (int64_t m = 0; m < nseg; ++m)
+        if (cu[m] < 0 || cu[m + 1] < cu[m]) return 1;       /* before anything is written */
     for (int64_t m = 0; m < nseg; ++m) {
         const int64_t n0 = cu[m], n1 = cu[m + 1];
-        if (n1 < n0) return 1;
 #pragma omp parallel for schedule(static)
         for (int64_t n = n0; n < n1; ++n) {
             double mu, r;
@@ -127,7 +128,7 @@ int lnmod_oracle_backward(const void *dy, const void *x, const void *scale, int 
     if (!cu || nseg < 0 || D <= 0) return 1;
     if (mod != LNMOD_ORACLE_PER_SEGMENT && mod != LNMOD_ORACLE_PER_TOKEN) return 1;
     for (int64_t m = 0; m < nseg; ++m)
-        if (cu[m + 1] < cu[m]) return 1;
+        if (cu[m] < 0 || cu[m + 1] < cu[m]) return 1;
     const int64_t T = nseg > 0 ? cu[nseg] : 0;
 
     /* the statistics of every row, recomputed here from x */
