@@ -14,6 +14,14 @@ int blocks_per_cu(int K) {
     return b < 1 ? 1 : b;
 }
 
+// Per-token modulation streams three inputs and three outputs per row, one row per step: twice
+// the waves.
+int tok_blocks_per_cu(int K) {
+    if (K == 1) return 8;
+    const int b = 10 / K;
+    return b < 1 ? 1 : b;
+}
+
 // Rows per block and step.  Two rows (about 8 KB of loads per wave and step, as much again
 // in flight for the next step) are robust; one row per step is faster on some runs and 35 %
 // slower on others, depending on the clocks the GPU happens to run at.  With per-token
@@ -36,6 +44,18 @@ void go_seg(const BwdArgs& a, int R, int64_t blocks, hipStream_t st) {
     else go_seg_r<Tag, VPL, K, 2, TOK>(a, blocks, st);
 }
 
+// The backward's split.  As the forward's, except that bf16 rows of 3 or 5 times 512 features
+// (D = 1536, 2560) are shared by 3 or 5 waves with one chunk per lane instead of being taken by
+// one wave or padded: every block writes a partial-sum slot, and a third as many blocks (of three
+// waves) means a third as many slots to write and add up.
+Split choose_split_bwd(int nchunks, int dtype) {
+    if (dtype == 0 && nchunks % 128 == 64) {
+        const int k = nchunks / 64;
+        if (k == 3 || k == 5) return {k, 1};
+    }
+    return choose_split(nchunks, dtype);
+}
+
 // VPL_WIDE: chunks per lane when several waves share a row (fixed by the dtype)
 template <typename Tag, int VPL_WIDE, bool TOK>
 void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t st) {
@@ -47,6 +67,11 @@ void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t
             case 4: go_seg<Tag, 4, 1, TOK>(a, R, blocks, st); break;
             default: go_seg<Tag, 6, 1, TOK>(a, R, blocks, st); break;
         }
+        return;
+    }
+    if (sp.VPL == 1) {                       // only choose_split_bwd produces these
+        if (sp.K == 3) go_seg<Tag, 1, 3, TOK>(a, R, blocks, st);
+        else go_seg<Tag, 1, 5, TOK>(a, R, blocks, st);
         return;
     }
     switch (sp.K) {
@@ -92,7 +117,7 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float* p, int64_t n) {
 
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Split sp = choose_split(static_cast<int>(D / E), dtype);
+    const Split sp = choose_split_bwd(static_cast<int>(D / E), dtype);
     const int R = rows_per_step(sp.K, D * (dtype == 0 ? 2 : 4));
     return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K), R, 90);
 }
@@ -102,7 +127,7 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
                           float* dscale, float* ws, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
-    const Split sp = choose_split(a.nchunks, p.dtype);
+    const Split sp = choose_split_bwd(a.nchunks, p.dtype);
     const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
@@ -134,7 +159,7 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, dshift, dscale, nullptr, E);
     const Split sp = choose_split(a.nchunks, p.dtype);
     const int R = rows_per_step_tok(sp.K, p.D * (p.dtype == 0 ? 2 : 4));
-    const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K), R, 90);
+    const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * tok_blocks_per_cu(sp.K), R, 90);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     if (p.dtype == 0) dispatch_seg<bf16_io, 2, true>(a, sp, R, pl.blocks, st);

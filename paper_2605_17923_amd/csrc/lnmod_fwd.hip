@@ -17,6 +17,13 @@ int fwd_blocks_per_cu(int K) {
     return b < 1 ? 1 : b;
 }
 
+// Per-token modulation streams three inputs per row and takes one row per step: twice the waves.
+int tok_blocks_per_cu(int K) {
+    if (K == 1) return 8;
+    const int b = 10 / K;
+    return b < 1 ? 1 : b;
+}
+
 FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
                   float* mean, float* rstd, int E) {
     FwdArgs a;
@@ -78,7 +85,8 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
     const Split sp = choose_split(a.nchunks, p.dtype);
     const bool per_segment = MODE == kModSegment || MODE == kModOnly;
     const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1,
-                                 static_cast<int64_t>(kNumCU) * fwd_blocks_per_cu(sp.K),
+                                 static_cast<int64_t>(kNumCU) *
+                                     (MODE == kModToken ? tok_blocks_per_cu(sp.K) : fwd_blocks_per_cu(sp.K)),
                                  MODE == kModToken ? kTokRows : kFwdRows, 20);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;

@@ -122,6 +122,42 @@ def test_varlen_leading_and_trailing_empty_segments():
     run_case(synth.make_inputs(4, lengths=(3000, 1, 1, 1, 2999), D=512))
 
 
+@pytest.mark.parametrize("seed,nseg,maxlen,D", [(1, 300, 40, 1536), (2, 97, 700, 5120), (3, 1000, 6, 512),
+                                                 (4, 40, 3000, 1536)])
+def test_varlen_many_random_segments(seed, nseg, maxlen, D):
+    # many short (and empty) segments: blocks that own no row of a (cluster, segment) piece,
+    # several clusters, pipelining across segment boundaries
+    rng = np.random.default_rng(seed)
+    lengths = rng.integers(0, maxlen + 1, nseg)
+    lengths[rng.random(nseg) < 0.15] = 0
+    run_case(synth.make_inputs(4, lengths=tuple(int(v) for v in lengths), D=D, seed=100 + seed),
+             label="random segments nseg=%d maxlen=%d D=%d" % (nseg, maxlen, D))
+
+
+def test_many_samples_fixed_length():
+    # enough samples that the blocks are split into several clusters
+    run_case(synth.make_inputs(2, B=200, S=97, D=1024), label="B=200 S=97 D=1024")
+    run_case(synth.make_inputs(0, B=33, S=50, D=5120, dtype="f32"), label="fp32 B=33 S=50 D=5120")
+
+
+def test_malformed_segment_table_stays_in_bounds():
+    # the table is only read on the device; whatever it holds, no access may leave the buffers.
+    # Afterwards a well-formed call must still be right.
+    inp = synth.make_inputs(4, lengths=(300, 200, 500), D=1536)
+    x = to_device(inp.x, "bf16")
+    dy = to_device(inp.dy, "bf16")
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    for table in ([0, 700, 100, 1000], [0, 5000, -7, 1000], [900, 900, 900, 900], [0, 0, 0, 0],
+                  [1000, 500, 200, 0]):
+        cu = torch.tensor(table, dtype=torch.int32, device="cuda")
+        y, mean, rstd = lnmod.forward_varlen(x, shift, scale, cu)
+        mean.fill_(0.0)
+        rstd.fill_(1.0)
+        lnmod.backward_varlen(dy, x, scale, cu, mean, rstd)
+        torch.cuda.synchronize()
+    run_case(inp, label="after malformed tables")
+
+
 @pytest.mark.parametrize("B,S", [(5, 77), (3, 1), (1, 1), (64, 9), (2, 2500)])
 def test_multi_sample_ranges_cross_blocks(B, S):
     run_case(synth.make_inputs(2, B=B, S=S), label="multi-sample B=%d S=%d" % (B, S))
