@@ -71,10 +71,24 @@ def cpu_baseline(D, sample_tokens, repeats=3):
         times.append(time.perf_counter() - t0)
     dt = sorted(times)[len(times) // 2]
     fwd_b, bwd_b = algorithmic_bytes(sample_tokens, D, 2)
-    return {"value": round((fwd_b + bwd_b) / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+    cores = oracle.num_threads()
+    one = None
+    if cores > 1:                                   # the same work on one thread, once
+        oracle.set_num_threads(1)
+        try:
+            t0 = time.perf_counter()
+            oracle.forward(inp.x, inp.shift, inp.scale, 1e-6, B=1, S=sample_tokens)
+            oracle.backward(inp.dy, inp.x, inp.scale, 1e-6, B=1, S=sample_tokens)
+            t1 = time.perf_counter() - t0
+        finally:
+            oracle.set_num_threads(cores)
+        one = {"value": round((fwd_b + bwd_b) / t1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+               "tokens_per_s": round(sample_tokens / t1), "seconds": round(t1, 3)}
+    return {"value": round((fwd_b + bwd_b) / dt / 1e9, 3), "unit": "GB/s", "cores": cores,
             "kind": "oracle", "tokens_per_s": round(sample_tokens / dt), "seconds": round(dt, 3),
             "sample": "%d of the workload's 75600 tokens (fwd+bwd, float64 C, OpenMP over rows), "
-                      "median of %d runs" % (sample_tokens, repeats)}
+                      "median of %d runs" % (sample_tokens, repeats),
+            "one_thread": one}
 
 
 def main():
@@ -151,17 +165,20 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
+    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    fwd_ms = sum(fwd_all) / K
+    bwd_ms = sum(bwd_all) / K
     ms_per_step = wall * 1e3 / K
     fwd_b, bwd_b = algorithmic_bytes(T, D, 2)
     value = (fwd_b + bwd_b) / (ms_per_step * 1e-3) / 1e9
 
-    def roof(nbytes, ms, kernel, traffic):
+    def roof(nbytes, ms, kernel, traffic, all_ms):
         a = nbytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "kernel": kernel, "achieved": round(a, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic,
-                "avg_launch_us": round(ms * 1e3, 2), "algorithmic_bytes": nbytes,
+                "avg_launch_us": round(ms * 1e3, 2), "median_launch_us": round(all_ms[len(all_ms) // 2] * 1e3, 2),
+                "min_launch_us": round(all_ms[0] * 1e3, 2), "algorithmic_bytes": nbytes,
                 "tokens_per_s": round(T / (ms * 1e-3))}
 
     out = {
@@ -175,8 +192,8 @@ def main():
         "frac_of_peak": round(value / PEAK_HBM_GBS, 4),
         "tokens_per_s": round(T / (ms_per_step * 1e-3)),
         "roofline": roof(bwd_b, bwd_ms, "lnmod_backward = bwd_seg_kernel + bwd_reduce_kernel "
-                                        "(durations summed)", MEASURED_TRAFFIC_BYTES["backward"]),
-        "roofline_fwd": roof(fwd_b, fwd_ms, "fwd_split_kernel", MEASURED_TRAFFIC_BYTES["forward"]),
+                                        "(durations summed)", MEASURED_TRAFFIC_BYTES["backward"], bwd_all),
+        "roofline_fwd": roof(fwd_b, fwd_ms, "fwd_split_kernel", MEASURED_TRAFFIC_BYTES["forward"], fwd_all),
     }
 
     if not args.no_extras:
