@@ -141,6 +141,54 @@ int lnmod_unfused_forward(const void* x, const void* shift, const void* scale,
                           void* xhat_tmp, void* y, float* mean, float* rstd, int dtype);
 int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/*
+ * Gated residual + LayerNorm-Modulate: the "Gate + Norm" chain the paper lists among its fused
+ * operators (Sec. 4.4) without defining it; defined here as a DiT block with adaptive LayerNorm
+ * has it around every LayerNorm-Modulate (Sec. 3.3):
+ *
+ *     h[n,d] = x[n,d] + gate[m,d]*u[n,d]     one fp32 fused multiply-add, rounded once (to nearest
+ *                                            even) to the I/O dtype and stored: the residual stream
+ *     y      = LayerNorm-Modulate of h as stored (formulas at the top), mean/rstd of h saved
+ *
+ * x, u, h, y: [N, D]; gate, shift, scale: [B, D] (cu_seqlens == NULL: B samples of S tokens;
+ * B_or_nseg = B, S_or_T = S) or [nseg, D] (cu_seqlens a device int32 [nseg+1] table as in
+ * lnmod_forward_varlen; B_or_nseg = nseg, S_or_T = T).  Errors as for lnmod_forward.
+ */
+int lnmod_gated_forward(const void* x, const void* u, const void* gate, const void* shift,
+                        const void* scale, const int32_t* cu_seqlens, int64_t B_or_nseg,
+                        int64_t S_or_T, int64_t D, float eps, void* stream,
+                        void* h, void* y, float* mean, float* rstd, int dtype);
+
+/*
+ * Backward of the above.  dy: gradient of y; dh: gradient that reaches h along the residual
+ * stream; h, mean, rstd: what lnmod_gated_forward produced; u, gate, scale: its inputs.
+ *
+ *     dx[n,d] = dh[n,d] + rstd_n*(g - c1 - hhat*c2)      (g, c1, c2 as at the top, with h for x)
+ *     du[n,d] = gate[m,d]*dx[n,d]
+ *     dgate[m,d] = sum_{n in m} u[n,d]*dx[n,d]    dshift, dscale as for lnmod_backward
+ *
+ * dx, du: [N, D] in the I/O dtype (dx is the gradient of x and of the incoming residual stream);
+ * dgate, dshift, dscale: float32 [B, D] / [nseg, D], zeros for empty segments; the sums use the
+ * fp32 dx before it is rounded.  workspace: lnmod_gated_backward_workspace_bytes() bytes, contents
+ * need no initialisation.  `eps` is only validated.  Errors as for lnmod_backward.
+ */
+int lnmod_gated_backward(const void* dy, const void* dh, const void* h, const void* u,
+                         const void* gate, const void* scale, const int32_t* cu_seqlens,
+                         int64_t B_or_nseg, int64_t S_or_T, int64_t D, float eps, void* stream,
+                         const float* mean, const float* rstd,
+                         void* dx, void* du, float* dgate, float* dshift, float* dscale,
+                         void* workspace, size_t workspace_bytes, int dtype);
+
+/* Bytes of device workspace lnmod_gated_backward needs (0 for invalid arguments).  Host-only. */
+size_t lnmod_gated_backward_workspace_bytes(int64_t B_or_nseg, int64_t total_tokens, int64_t D);
+
+/*
+ * Measurement comparator: only h = x + gate*u (per-sample gate [B, D]), the first kernel of the
+ * unfused chain "residual update, then lnmod_forward on h".
+ */
+int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t B, int64_t S,
+                        int64_t D, void* stream, void* h, int dtype);
+
 #ifdef __cplusplus
 }
 #endif

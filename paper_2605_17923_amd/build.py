@@ -14,7 +14,8 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIBRARY = os.path.join(HERE, "liblnmod.so")
 
-SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_misc.hip", "lnmod_api.cpp"]
+SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated_bwd.hip",
+           "lnmod_misc.hip", "lnmod_api.cpp"]
 HEADERS = [os.path.join(CSRC, "lnmod_kernels.hpp"), os.path.join(CSRC, "lnmod_launch.hpp"),
            os.path.join(INCLUDE, "lnmod.h")]
 
@@ -53,7 +54,7 @@ def _compile(src: str, force: bool) -> str:
 def build_library(force: bool = False, verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link liblnmod.so; returns its path."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as pool:
         objs = list(pool.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIBRARY, objs):
         tmp = LIBRARY + ".tmp.%d" % os.getpid()

@@ -97,6 +97,29 @@ int backward_impl(const void* dy, const void* x, const void* scale, const int32_
     return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
 }
 
+size_t gated_workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
+    int64_t slots = 0;
+    for (int dtype = 0; dtype < 2; ++dtype) {
+        if (D % (dtype == 0 ? 8 : 4) != 0) continue;
+        const lnmod::RowPlan pl = lnmod::gated_bwd_plan(T, nseg, D, dtype);
+        const int64_t s = lnmod::bwd_slots(pl, nseg);
+        if (s > slots) slots = s;
+    }
+    return static_cast<size_t>(slots) * 3u * static_cast<size_t>(D) * sizeof(float);
+}
+
+// (segments, tokens per sample, total tokens) of a gated call, or false on overflow
+bool gated_shape(const int32_t* cu, int64_t B_or_nseg, int64_t S_or_T, int64_t* S, int64_t* T) {
+    if (cu) {
+        *S = 0;
+        *T = S_or_T;
+        return true;
+    }
+    *S = S_or_T;
+    *T = total_tokens(B_or_nseg, S_or_T);
+    return *T >= 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -171,6 +194,83 @@ int lnmod_unfused_forward(const void* x, const void* shift, const void* scale, i
     const Problem p{dtype, nullptr, B, S, T, D, eps};
     const hipError_t e = lnmod::launch_unfused(p, x, shift, scale, xhat_tmp, y, mean, rstd,
                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_gated_forward(const void* x, const void* u, const void* gate, const void* shift,
+                        const void* scale, const int32_t* cu_seqlens, int64_t B_or_nseg,
+                        int64_t S_or_T, int64_t D, float eps, void* stream, void* h, void* y,
+                        float* mean, float* rstd, int dtype) {
+    int64_t S, T;
+    if (!gated_shape(cu_seqlens, B_or_nseg, S_or_T, &S, &T)) return LNMOD_EINVAL;
+    const int st = check_shape(B_or_nseg, S_or_T, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    if (T == 0) return LNMOD_OK;
+    if (B_or_nseg == 0) return LNMOD_EINVAL;
+    if (!x || !u || !gate || !shift || !scale || !h || !y || !mean || !rstd) return LNMOD_EINVAL;
+    if (!aligned16(x) || !aligned16(u) || !aligned16(gate) || !aligned16(shift) || !aligned16(scale) ||
+        !aligned16(h) || !aligned16(y))
+        return LNMOD_EALIGN;
+    const Problem p{dtype, cu_seqlens, B_or_nseg, S, T, D, eps};
+    const hipError_t e = lnmod::launch_gated_fwd(p, x, u, gate, shift, scale, h, y, mean, rstd,
+                                                 static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_gated_backward(const void* dy, const void* dh, const void* h, const void* u,
+                         const void* gate, const void* scale, const int32_t* cu_seqlens,
+                         int64_t B_or_nseg, int64_t S_or_T, int64_t D, float eps, void* stream,
+                         const float* mean, const float* rstd, void* dx, void* du, float* dgate,
+                         float* dshift, float* dscale, void* workspace, size_t workspace_size,
+                         int dtype) {
+    int64_t S, T;
+    if (!gated_shape(cu_seqlens, B_or_nseg, S_or_T, &S, &T)) return LNMOD_EINVAL;
+    const int st = check_shape(B_or_nseg, S_or_T, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    const hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (T == 0) {
+        if (B_or_nseg > 0) {                                  // empty sums are zeros
+            if (!dgate || !dshift || !dscale) return LNMOD_EINVAL;
+            hipError_t e = lnmod::launch_zero_f32(dgate, B_or_nseg * D, hs);
+            if (e == hipSuccess) e = lnmod::launch_zero_f32(dshift, B_or_nseg * D, hs);
+            if (e == hipSuccess) e = lnmod::launch_zero_f32(dscale, B_or_nseg * D, hs);
+            return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+        }
+        return LNMOD_OK;
+    }
+    if (B_or_nseg == 0) return LNMOD_EINVAL;
+    if (!dy || !dh || !h || !u || !gate || !scale || !mean || !rstd || !dx || !du || !dgate ||
+        !dshift || !dscale)
+        return LNMOD_EINVAL;
+    if (!aligned16(dy) || !aligned16(dh) || !aligned16(h) || !aligned16(u) || !aligned16(gate) ||
+        !aligned16(scale) || !aligned16(dx) || !aligned16(du))
+        return LNMOD_EALIGN;
+    if (!workspace || workspace_size < gated_workspace_bytes(B_or_nseg, T, D)) return LNMOD_EWORKSPACE;
+    if (!aligned16(workspace)) return LNMOD_EALIGN;
+    const Problem p{dtype, cu_seqlens, B_or_nseg, S, T, D, eps};
+    const hipError_t e = lnmod::launch_gated_bwd(p, dy, dh, h, u, gate, scale, mean, rstd, dx, du,
+                                                 dgate, dshift, dscale,
+                                                 static_cast<float*>(workspace), hs);
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+size_t lnmod_gated_backward_workspace_bytes(int64_t B_or_nseg, int64_t total, int64_t D) {
+    if (B_or_nseg < 0 || total < 0 || total >= (int64_t(1) << 31)) return 0;
+    if (D < 8 || D > lnmod::kMaxD || D % 4 != 0) return 0;
+    return gated_workspace_bytes(B_or_nseg, total, D);
+}
+
+int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t B, int64_t S,
+                        int64_t D, void* stream, void* h, int dtype) {
+    const int64_t T = total_tokens(B, S);
+    if (T < 0) return LNMOD_EINVAL;
+    const int st = check_shape(B, S, D, 1.0f, dtype, T);
+    if (st != LNMOD_OK) return st;
+    if (T == 0) return LNMOD_OK;
+    if (!x || !u || !gate || !h) return LNMOD_EINVAL;
+    if (!aligned16(x) || !aligned16(u) || !aligned16(gate) || !aligned16(h)) return LNMOD_EALIGN;
+    const Problem p{dtype, nullptr, B, S, T, D, 1.0f};
+    const hipError_t e = lnmod::launch_gate_residual(p, x, u, gate, h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
 }
 

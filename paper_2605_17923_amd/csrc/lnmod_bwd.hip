@@ -44,18 +44,6 @@ void go_seg(const BwdArgs& a, int R, int64_t blocks, hipStream_t st) {
     else go_seg_r<Tag, VPL, K, 2, TOK>(a, blocks, st);
 }
 
-// The backward's split.  As the forward's, except that bf16 rows of 3 or 5 times 512 features
-// (D = 1536, 2560) are shared by 3 or 5 waves with one chunk per lane instead of being taken by
-// one wave or padded: every block writes a partial-sum slot, and a third as many blocks (of three
-// waves) means a third as many slots to write and add up.
-Split choose_split_bwd(int nchunks, int dtype) {
-    if (dtype == 0 && nchunks % 128 == 64) {
-        const int k = nchunks / 64;
-        if (k == 3 || k == 5) return {k, 1};
-    }
-    return choose_split(nchunks, dtype);
-}
-
 // VPL_WIDE: chunks per lane when several waves share a row (fixed by the dtype)
 template <typename Tag, int VPL_WIDE, bool TOK>
 void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t st) {

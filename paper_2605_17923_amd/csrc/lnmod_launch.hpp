@@ -85,6 +85,18 @@ inline Split choose_split(int nchunks, int dtype) {
     return {k, per_feat16};
 }
 
+// The backward's split.  As the forward's, except that bf16 rows of 3 or 5 times 512 features
+// (D = 1536, 2560) are shared by 3 or 5 waves with one chunk per lane instead of being taken by
+// one wave or padded: every block writes a partial-sum slot, and a third as many blocks (of three
+// waves) means a third as many slots to write and add up.
+inline Split choose_split_bwd(int nchunks, int dtype) {
+    if (dtype == 0 && nchunks % 128 == 64) {
+        const int k = nchunks / 64;
+        if (k == 3 || k == 5) return {k, 1};
+    }
+    return choose_split(nchunks, dtype);
+}
+
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
 // kernel's grid and tells the second pass which partial-sum slots belong to a segment.
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
@@ -103,6 +115,18 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
 hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* xhat, void* y, float* mean, float* rstd, hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+
+// Gated residual + LayerNorm-Modulate (per-sample / per-segment gate, shift, scale).
+RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
+hipError_t launch_gated_fwd(const Problem& p, const void* x, const void* u, const void* gate,
+                            const void* shift, const void* scale, void* h, void* y, float* mean,
+                            float* rstd, hipStream_t st);
+hipError_t launch_gate_residual(const Problem& p, const void* x, const void* u, const void* gate,
+                                void* h, hipStream_t st);
+hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, const void* h,
+                            const void* u, const void* gate, const void* scale, const float* mean,
+                            const float* rstd, void* dx, void* du, float* dgate, float* dshift,
+                            float* dscale, float* ws, hipStream_t st);
 hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t st);
 
 }  // namespace lnmod

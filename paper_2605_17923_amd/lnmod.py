@@ -21,7 +21,8 @@ LIBRARY = os.path.join(_HERE, "liblnmod.so")
 
 EXPORTS = ("lnmod_forward", "lnmod_backward", "lnmod_forward_varlen", "lnmod_backward_varlen",
            "lnmod_backward_workspace_bytes", "lnmod_status_string", "lnmod_unfused_forward",
-           "lnmod_copy")
+           "lnmod_copy", "lnmod_gated_forward", "lnmod_gated_backward",
+           "lnmod_gated_backward_workspace_bytes", "lnmod_gate_residual")
 
 _lib = None
 
@@ -61,6 +62,16 @@ def library() -> ctypes.CDLL:
     lib.lnmod_unfused_forward.argtypes = [vp, vp, vp, i64, i64, i64, f32, vp, vp, vp, vp, vp, cint]
     lib.lnmod_copy.restype = cint
     lib.lnmod_copy.argtypes = [vp, vp, sz, vp]
+    lib.lnmod_gated_forward.restype = cint
+    lib.lnmod_gated_forward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp,
+                                        vp, vp, vp, vp, cint]
+    lib.lnmod_gated_backward.restype = cint
+    lib.lnmod_gated_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp,
+                                         vp, vp, vp, vp, vp, vp, vp, vp, sz, cint]
+    lib.lnmod_gated_backward_workspace_bytes.restype = sz
+    lib.lnmod_gated_backward_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.lnmod_gate_residual.restype = cint
+    lib.lnmod_gate_residual.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, cint]
     _lib = lib
     return lib
 
@@ -124,6 +135,31 @@ def lnmod_unfused_forward(x, shift, scale, B, S, D, eps, stream, xhat_tmp, y, me
 
 def lnmod_copy(src, dst, nbytes, stream):
     return library().lnmod_copy(_p(src), _p(dst), nbytes, stream)
+
+
+def lnmod_gated_forward(x, u, gate, shift, scale, cu_seqlens, B_or_nseg, S_or_T, D, eps, stream,
+                        h, y, mean, rstd, dtype):
+    return library().lnmod_gated_forward(_p(x), _p(u), _p(gate), _p(shift), _p(scale),
+                                         _p(cu_seqlens), B_or_nseg, S_or_T, D, eps, stream,
+                                         _p(h), _p(y), _p(mean), _p(rstd), dtype)
+
+
+def lnmod_gated_backward(dy, dh, h, u, gate, scale, cu_seqlens, B_or_nseg, S_or_T, D, eps, stream,
+                         mean, rstd, dx, du, dgate, dshift, dscale, workspace, workspace_bytes,
+                         dtype):
+    return library().lnmod_gated_backward(_p(dy), _p(dh), _p(h), _p(u), _p(gate), _p(scale),
+                                          _p(cu_seqlens), B_or_nseg, S_or_T, D, eps, stream,
+                                          _p(mean), _p(rstd), _p(dx), _p(du), _p(dgate),
+                                          _p(dshift), _p(dscale), _p(workspace), workspace_bytes,
+                                          dtype)
+
+
+def lnmod_gated_backward_workspace_bytes(B_or_nseg, total_tokens, D):
+    return int(library().lnmod_gated_backward_workspace_bytes(B_or_nseg, total_tokens, D))
+
+
+def lnmod_gate_residual(x, u, gate, B, S, D, stream, h, dtype):
+    return library().lnmod_gate_residual(_p(x), _p(u), _p(gate), B, S, D, stream, _p(h), dtype)
 
 
 # ---- conveniences: allocate outputs with torch, raise on a non-zero status ----------------------
@@ -208,3 +244,49 @@ def backward_varlen(dy, x, scale, cu_seqlens, mean, rstd, eps=1e-6, stream=None,
                                  _stream_handle(stream), mean, rstd, dx, dshift, dscale, ws,
                                  ws.numel(), _dtype_code(x)), "lnmod_backward_varlen")
     return dx, dshift, dscale
+
+
+def gated_workspace(B_or_nseg, total_tokens, D, device):
+    import torch
+    n = lnmod_gated_backward_workspace_bytes(B_or_nseg, total_tokens, D)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def _gated_shape(x, cu_seqlens):
+    if cu_seqlens is None:
+        B, S, D = x.shape
+        return B, S, B * S, D
+    T, D = x.shape
+    return cu_seqlens.numel() - 1, T, T, D
+
+
+def gated_forward(x, u, gate, shift, scale, cu_seqlens=None, eps=1e-6, stream=None):
+    """h = x + gate*u (stored), y = LayerNorm-Modulate(h).  x, u: [B,S,D] with gate/shift/scale
+    [B,D], or packed [T,D] with cu_seqlens (device int32 [nseg+1]) and [nseg,D] modulation rows.
+    -> h, y, mean, rstd."""
+    import torch
+    n, s_or_t, T, D = _gated_shape(x, cu_seqlens)
+    h, y = torch.empty_like(x), torch.empty_like(x)
+    mean = torch.empty(T, dtype=torch.float32, device=x.device)
+    rstd = torch.empty(T, dtype=torch.float32, device=x.device)
+    _check(lnmod_gated_forward(x, u, gate, shift, scale, cu_seqlens, n, s_or_t, D, eps,
+                               _stream_handle(stream), h, y, mean, rstd, _dtype_code(x)),
+           "lnmod_gated_forward")
+    return h, y, mean, rstd
+
+
+def gated_backward(dy, dh, h, u, gate, scale, mean, rstd, cu_seqlens=None, eps=1e-6, stream=None,
+                   ws=None):
+    """-> dx, du (I/O dtype) and dgate, dshift, dscale (float32 [B,D] / [nseg,D])."""
+    import torch
+    n, s_or_t, T, D = _gated_shape(h, cu_seqlens)
+    dx, du = torch.empty_like(h), torch.empty_like(h)
+    dgate = torch.empty(n, D, dtype=torch.float32, device=h.device)
+    dshift = torch.empty(n, D, dtype=torch.float32, device=h.device)
+    dscale = torch.empty(n, D, dtype=torch.float32, device=h.device)
+    if ws is None:
+        ws = gated_workspace(n, T, D, h.device)
+    _check(lnmod_gated_backward(dy, dh, h, u, gate, scale, cu_seqlens, n, s_or_t, D, eps,
+                                _stream_handle(stream), mean, rstd, dx, du, dgate, dshift, dscale,
+                                ws, ws.numel(), _dtype_code(h)), "lnmod_gated_backward")
+    return dx, du, dgate, dshift, dscale

@@ -167,3 +167,24 @@ def make_inputs(index: int, *, S: Optional[int] = None, B: Optional[int] = None,
     w_out = Workload(**{**w.__dict__, "dtype": dt, "B": B, "S": S_out, "D": D})
     return Inputs(w_out, x, shift, scale, dy, cu.astype(np.int32), B, S_out, D,
                   lengths=lengths, length_seed=length_seed)
+
+
+@dataclass
+class GatedExtras:
+    """The additional inputs of the gated residual + LayerNorm-Modulate operator."""
+    u: np.ndarray                   # [T, D] branch output
+    gate: np.ndarray                # [B, D] / [nseg, D]
+    dh: np.ndarray                  # [T, D] gradient arriving along the residual stream
+
+
+def make_gated_extras(inp: Inputs, seed: int) -> GatedExtras:
+    """u ~ N(0, 1), gate ~ N(0, 0.3), dh ~ N(0, 1) for the token layout of `inp`, rounded to bf16
+    when the workload's I/O type is bf16."""
+    rng = np.random.default_rng(seed)
+    T, D = inp.x.shape
+    u = _normal(rng, (T, D), 0.0, 1.0)
+    gate = _normal(rng, (inp.B, D), 0.0, 0.3)
+    dh = _normal(rng, (T, D), 0.0, 1.0)
+    if inp.workload.dtype == "bf16":
+        u, gate, dh = round_to_bf16(u), round_to_bf16(gate), round_to_bf16(dh)
+    return GatedExtras(u, gate, dh)

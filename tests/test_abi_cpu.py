@@ -143,6 +143,53 @@ def test_copy_and_unfused_reject_bad_arguments(lib):
     assert u(A, A, A, 2, 4, 63, 1e-6, None, A, A, A, A, 0) == lnmod.LNMOD_EUNSUPPORTED
 
 
+def gfwd(x=A, u=A, gate=A, shift=A, scale=A, cu=None, n=2, s=4, D=64, eps=1e-6, h=A, y=A, mean=A,
+         rstd=A, dtype=0):
+    return lnmod.lnmod_gated_forward(x, u, gate, shift, scale, cu, n, s, D, eps, None, h, y, mean,
+                                     rstd, dtype)
+
+
+def gbwd(dy=A, dh=A, h=A, u=A, gate=A, scale=A, cu=None, n=2, s=4, D=64, eps=1e-6, mean=A, rstd=A,
+         dx=A, du=A, dgate=A, dshift=A, dscale=A, ws=A, ws_bytes=1 << 40, dtype=0):
+    return lnmod.lnmod_gated_backward(dy, dh, h, u, gate, scale, cu, n, s, D, eps, None, mean, rstd,
+                                      dx, du, dgate, dshift, dscale, ws, ws_bytes, dtype)
+
+
+def test_gated_rejects_bad_arguments(lib):
+    E = lnmod
+    assert gfwd(u=None) == E.LNMOD_EINVAL and gfwd(gate=None) == E.LNMOD_EINVAL
+    assert gfwd(h=None) == E.LNMOD_EINVAL and gfwd(mean=None) == E.LNMOD_EINVAL
+    assert gfwd(eps=0.0) == E.LNMOD_EINVAL and gfwd(dtype=2) == E.LNMOD_EINVAL
+    assert gfwd(n=-1) == E.LNMOD_EINVAL and gfwd(n=1 << 40, s=1 << 40) == E.LNMOD_EINVAL
+    assert gfwd(D=63) == E.LNMOD_EUNSUPPORTED and gfwd(D=8200) == E.LNMOD_EUNSUPPORTED
+    assert gfwd(D=68, dtype=0) == E.LNMOD_EUNSUPPORTED
+    assert gfwd(u=A + 8) == E.LNMOD_EALIGN and gfwd(h=A + 2) == E.LNMOD_EALIGN
+    assert gfwd(n=2, s=0) == E.LNMOD_OK and gfwd(n=0, s=0) == E.LNMOD_OK
+    assert gfwd(cu=A, n=0, s=5) == E.LNMOD_EINVAL            # tokens that belong to no segment
+    assert gbwd(dh=None) == E.LNMOD_EINVAL and gbwd(du=None) == E.LNMOD_EINVAL
+    assert gbwd(dgate=None) == E.LNMOD_EINVAL and gbwd(eps=float("nan")) == E.LNMOD_EINVAL
+    assert gbwd(D=12, dtype=0) == E.LNMOD_EUNSUPPORTED
+    assert gbwd(dy=A + 4) == E.LNMOD_EALIGN and gbwd(du=A + 4) == E.LNMOD_EALIGN
+    assert gbwd(ws=None) == E.LNMOD_EWORKSPACE and gbwd(ws_bytes=16) == E.LNMOD_EWORKSPACE
+    assert gbwd(ws=A + 4) == E.LNMOD_EALIGN
+    assert gbwd(n=0, s=0) == E.LNMOD_OK
+    g = lnmod.lnmod_gate_residual
+    assert g(A, None, A, 2, 4, 64, None, A, 0) == E.LNMOD_EINVAL
+    assert g(A, A, A, 2, 4, 60, None, A, 0) == E.LNMOD_EUNSUPPORTED
+    assert g(A, A, A + 1, 2, 4, 64, None, A, 0) == E.LNMOD_EALIGN
+
+
+def test_gated_workspace_query(lib):
+    q = lnmod.lnmod_gated_backward_workspace_bytes
+    assert q(-1, 10, 64) == 0 and q(1, -1, 64) == 0 and q(1, 10, 66) == 0
+    slot = 3 * 5120 * 4                       # dshift, dscale and dgate rows in fp32
+    n = q(1, 75600, 5120)
+    assert n % slot == 0 and n >= slot
+    assert 2 * n <= 0.05 * 75600 * 12 * 5120   # small beside the backward's own 12*D bytes per token
+    m = q(24, 152880, 5120)
+    assert m % slot == 0 and m >= 24 * slot
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(lnmod, "_lib", None)
     monkeypatch.setattr(lnmod, "LIBRARY", os.path.join(tmp_path, "nope.so"))

@@ -1,0 +1,168 @@
+"""GPU parity of the gated residual + LayerNorm-Modulate kernels (called through the C ABI)
+against the float64 oracle in oracle/gated_oracle.c on the same seeded inputs.
+
+h is a quantised value (one fp32 fused multiply-add rounded to the I/O type), so both sides take
+that rounding in the same precision and h is compared bit for bit; y, the statistics and every
+gradient are compared with the tolerances of the LayerNorm-Modulate tests.  The backward is fed
+the h, mean and rstd the GPU forward produced; the oracle reads the same h and recomputes the
+statistics in float64."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gated_oracle as go
+from paper_2605_17923_amd import lnmod, synth
+from parity_util import check_f32_tensor, check_io_tensor, check_stats, to_device, to_host64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lnmod.library()
+    yield
+    torch.cuda.synchronize()
+
+
+def run_gated(inp, seed, sample_rows=None, label=""):
+    w = inp.workload
+    dt = w.dtype
+    T, D, B = inp.T, inp.D, inp.B
+    ex = synth.make_gated_extras(inp, seed)
+    print("gated case", label or w.name, "dtype", dt, "T", T, "D", D, "B", B, "varlen", w.varlen, flush=True)
+    x, u, dy, dh = (to_device(a, dt) for a in (inp.x, ex.u, inp.dy, ex.dh))
+    gate, shift, scale = (to_device(a, dt) for a in (ex.gate, inp.shift, inp.scale))
+    cu64 = inp.cu_seqlens.astype(np.int64)
+    cu_dev = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda() if w.varlen else None
+    if w.varlen:
+        h, y, mean, rstd = lnmod.gated_forward(x, u, gate, shift, scale, cu_dev, w.eps)
+    else:
+        h, y, mean, rstd = lnmod.gated_forward(x.view(B, inp.S, D), u.view(B, inp.S, D), gate, shift, scale,
+                                               None, w.eps)
+    torch.cuda.synchronize()
+    quant = go.QUANT_BF16 if dt == "bf16" else go.QUANT_F32
+
+    rows = np.arange(T) if sample_rows is None else np.asarray(sample_rows, dtype=np.int64)
+    rows_t = torch.from_numpy(rows).cuda()
+    seg_of = np.searchsorted(cu64, rows, side="right") - 1
+    if sample_rows is None:
+        h64, y64, mean64, rstd64 = go.forward(inp.x, ex.u, ex.gate, inp.shift, inp.scale, w.eps, cu=cu64,
+                                              quant=quant)
+    else:                                   # rows are independent in the forward
+        h64, y64 = np.empty((rows.size, D)), np.empty((rows.size, D))
+        mean64, rstd64 = np.empty(rows.size), np.empty(rows.size)
+        for m in np.unique(seg_of):
+            sel = np.nonzero(seg_of == m)[0]
+            a, b, c, d = go.forward(inp.x[rows[sel]], ex.u[rows[sel]], ex.gate[m:m + 1], inp.shift[m:m + 1],
+                                    inp.scale[m:m + 1], w.eps, B=1, S=sel.size, quant=quant)
+            h64[sel], y64[sel], mean64[sel], rstd64[sel] = a, b, c, d
+    h_got = to_host64(h.reshape(T, D)[rows_t])
+    if dt == "bf16":
+        assert np.array_equal(h_got, h64), "h: %d elements differ from the rounded reference" % int(
+            (h_got != h64).sum())
+    else:
+        # fp32: the float64 sum of a 48-bit product and a 24-bit addend can itself round
+        ulp = np.spacing(np.abs(h64).astype(np.float32)).astype(np.float64)
+        assert np.all(np.abs(h_got - h64) <= ulp), "h: beyond one float32 ulp"
+        assert np.mean(h_got != h64) < 1e-4
+    check_io_tensor("y", y.reshape(T, D)[rows_t], y64, dt)
+    check_stats(mean.reshape(T)[rows_t], rstd.reshape(T)[rows_t], mean64, rstd64)
+
+    if w.varlen:
+        dx, du, dgate, dsh, dsc = lnmod.gated_backward(dy, dh, h, u, gate, scale, mean, rstd, cu_dev, w.eps)
+    else:
+        v = lambda t: t.view(B, inp.S, D)
+        dx, du, dgate, dsh, dsc = lnmod.gated_backward(v(dy), v(dh), v(h), v(u), gate, scale, mean, rstd,
+                                                       None, w.eps)
+    torch.cuda.synchronize()
+    h_host = h.reshape(T, D).to(torch.float32).cpu().numpy()        # exactly what the GPU backward read
+    dx64, du64, dg64, dsh64, dsc64 = go.backward(inp.dy, ex.dh, h_host, ex.u, ex.gate, inp.scale, w.eps, cu=cu64)
+    check_io_tensor("dx", dx.reshape(T, D)[rows_t], dx64[rows], dt)
+    check_io_tensor("du", du.reshape(T, D)[rows_t], du64[rows], dt)
+    check_f32_tensor("dgate", dgate, dg64)
+    check_f32_tensor("dshift", dsh, dsh64)
+    check_f32_tensor("dscale", dsc, dsc64)
+
+
+def test_gated_tiny_fp32():
+    run_gated(synth.make_inputs(0), 2001)
+
+
+def test_gated_bf16_d5120_outliers():
+    run_gated(synth.make_inputs(2, S=1031), 2002)
+
+
+def test_gated_bf16_d1536_three_samples():
+    run_gated(synth.make_inputs(1, B=3, S=701, with_dy=True), 2003)
+
+
+@pytest.mark.parametrize("D,dtype", [(1528, "bf16"), (200, "bf16"), (8, "bf16"), (8192, "bf16"), (2560, "bf16"),
+                                     (3072, "bf16"), (100, "f32"), (5120, "f32"), (8192, "f32"), (1100, "f32")])
+def test_gated_hidden_sizes(D, dtype):
+    run_gated(synth.make_inputs(0, B=2, S=67, D=D, dtype=dtype), 2100 + D, label="D=%d %s" % (D, dtype))
+
+
+def test_gated_varlen_with_empty_segments():
+    lengths = (37, 0, 1560, 5, 819, 1, 0, 0, 300, 64, 2, 777, 0)
+    run_gated(synth.make_inputs(4, lengths=lengths), 2004)
+    run_gated(synth.make_inputs(4, lengths=(0, 0, 129, 0), D=1536), 2005)
+    run_gated(synth.make_inputs(4, lengths=(1,), D=512), 2006)
+
+
+@pytest.mark.parametrize("seed,nseg,maxlen,D", [(1, 300, 40, 1536), (2, 97, 700, 5120), (3, 1000, 6, 512)])
+def test_gated_varlen_many_random_segments(seed, nseg, maxlen, D):
+    rng = np.random.default_rng(seed)
+    lengths = rng.integers(0, maxlen + 1, nseg)
+    lengths[rng.random(nseg) < 0.15] = 0
+    run_gated(synth.make_inputs(4, lengths=tuple(int(v) for v in lengths), D=D, seed=300 + seed), 2200 + seed,
+              label="random segments nseg=%d maxlen=%d D=%d" % (nseg, maxlen, D))
+
+
+def test_gated_many_samples():
+    run_gated(synth.make_inputs(2, B=200, S=97, D=1024), 2007, label="B=200 S=97 D=1024")
+
+
+def test_gated_zero_gate_matches_plain_forward():
+    # gate = 0: h must equal x bit for bit and y, mean, rstd must equal lnmod_forward's
+    inp = synth.make_inputs(2, S=515)
+    x = to_device(inp.x, "bf16").view(1, 515, 5120)
+    u = to_device(synth.make_gated_extras(inp, 5).u, "bf16").view(1, 515, 5120)
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    h, y, mean, rstd = lnmod.gated_forward(x, u, torch.zeros_like(shift), shift, scale)
+    y2, mean2, rstd2 = lnmod.forward(x, shift, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(h, x) and torch.equal(y, y2)
+    assert torch.equal(mean, mean2.reshape(-1)) and torch.equal(rstd, rstd2.reshape(-1))
+
+
+def test_gated_results_repeat_bit_for_bit():
+    inp = synth.make_inputs(4, lengths=(700, 0, 1300, 41), D=5120)
+    ex = synth.make_gated_extras(inp, 9)
+    dev = {k: to_device(v, "bf16") for k, v in dict(x=inp.x, u=ex.u, dy=inp.dy, dh=ex.dh, gate=ex.gate,
+                                                    shift=inp.shift, scale=inp.scale).items()}
+    cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+    outs = []
+    for _ in range(2):
+        h, y, mean, rstd = lnmod.gated_forward(dev["x"], dev["u"], dev["gate"], dev["shift"], dev["scale"], cu)
+        outs.append((h, y, mean, rstd) + lnmod.gated_backward(dev["dy"], dev["dh"], h, dev["u"], dev["gate"],
+                                                              dev["scale"], mean, rstd, cu))
+    torch.cuda.synchronize()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def _sample_rows(T, cu, n=1200, seed=11):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, T, n).tolist())
+    rows.update([0, 1, 2, 3, T - 1, T - 2, T - 3, T - 4])
+    for c in np.asarray(cu, dtype=np.int64):
+        for d in (-2, -1, 0, 1):
+            if 0 <= c + d < T:
+                rows.add(int(c + d))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def test_gated_config2_full_size():
+    inp = synth.make_inputs(2)
+    run_gated(inp, 2008, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
