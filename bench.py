@@ -289,6 +289,47 @@ def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=Non
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
 
 
+def _run_gated(lnmod, torch, stream, st, dev, T, D):
+    """The gated residual + LayerNorm-Modulate fusion on the workload's shape (bf16, one sample):
+    fused forward against the unfused chain (residual kernel, then lnmod_forward on h), and the
+    fused backward.  Algorithmic bytes per token: forward 8D+8 (x, u in; h, y, statistics out),
+    backward 12D+8 (dy, dh, h, u, statistics in; dx, du out)."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    x, u, dy, dh = (_randn_bf16(torch, g, (T, D), dev) for _ in range(4))
+    gate, shift, scale = (_randn_bf16(torch, g, (1, D), dev, 0.2) for _ in range(3))
+    h, y, dx, du = (torch.empty_like(x) for _ in range(4))
+    mean = torch.empty(T, dtype=torch.float32, device=dev)
+    rstd = torch.empty(T, dtype=torch.float32, device=dev)
+    dg, dsh, dsc = (torch.empty(1, D, dtype=torch.float32, device=dev) for _ in range(3))
+    ws = lnmod.gated_workspace(1, T, D, dev)
+    BF = lnmod.LNMOD_BF16
+
+    def fused_fwd():
+        rc = lnmod.lnmod_gated_forward(x, u, gate, shift, scale, None, 1, T, D, 1e-6, st, h, y, mean, rstd, BF)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    def unfused_fwd():
+        rc = lnmod.lnmod_gate_residual(x, u, gate, 1, T, D, st, h, BF)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+        rc = lnmod.lnmod_forward(h, shift, scale, 1, T, D, 1e-6, st, y, mean, rstd, BF, lnmod.LNMOD_PER_SAMPLE)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    def fused_bwd():
+        rc = lnmod.lnmod_gated_backward(dy, dh, h, u, gate, scale, None, 1, T, D, 1e-6, st, mean, rstd, dx, du,
+                                        dg, dsh, dsc, ws, ws.numel(), BF)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    f_ms = _time_ms(torch, stream, fused_fwd)
+    uf_ms = _time_ms(torch, stream, unfused_fwd)
+    b_ms = _time_ms(torch, stream, fused_bwd)
+    fwd_b, bwd_b = T * (8 * D + 8), T * (12 * D + 8)
+    return {"workload": "gated residual + LN-Modulate, bf16 B=1 S=%d D=%d" % (T, D),
+            "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
+            "unfused_fwd_us": round(uf_ms * 1e3, 1), "fused_vs_unfused_fwd_speedup": round(uf_ms / f_ms, 3),
+            "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
+
+
 def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
     """Context figures: a plain copy as the practical bandwidth ceiling, the unfused two-kernel
     forward (LayerNorm -> xhat in HBM -> modulate), the other workload shapes and the token
@@ -318,6 +359,7 @@ def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused
         _run_workload(lnmod, torch, stream, st, dev, "configs[4] varlen 24 segments T=%d D=5120" % sum(lengths),
                       24, 0, 5120, PS, lengths=lengths, seed=1005),
     ]
+    res["gated"] = _run_gated(lnmod, torch, stream, st, dev, T, D)
     grid = []
     for n in range(8000, 64001, 8000):
         r = _run_workload(lnmod, torch, stream, st, dev, "N=%d" % n, 1, n, 5120, PS, seed=n)
