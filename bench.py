@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run lnmod_copy on a buffer of the workload's size (a kernel of known "
                          "traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--gated-only", action="store_true",
+                    help="only time the gated residual + LayerNorm-Modulate fusion on the workload's "
+                         "shape (for profiling its kernels; not the headline metric)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the copy ceiling, the unfused comparison and the D=1536 forward")
     args = ap.parse_args()
@@ -126,6 +129,10 @@ def main():
         ms = _time_ms(torch, stream, lambda: lnmod.lnmod_copy(src, dst, nbytes, stream.cuda_stream), iters=args.steps)
         print(json.dumps({"kernel": "copy16_kernel", "bytes_read": nbytes, "bytes_written": nbytes,
                           "avg_launch_us": round(ms * 1e3, 2), "GBs": _gbs(2 * nbytes, ms)}))
+        return
+    if args.gated_only:
+        stream = torch.cuda.current_stream()
+        print(json.dumps(_run_gated(lnmod, torch, stream, stream.cuda_stream, dev, T, D, iters=args.steps)))
         return
     x, dy, shift, scale = make_device_inputs(T, D, 1003, dev)
     y, dx = torch.empty_like(x), torch.empty_like(x)
@@ -289,7 +296,7 @@ def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=Non
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
 
 
-def _run_gated(lnmod, torch, stream, st, dev, T, D):
+def _run_gated(lnmod, torch, stream, st, dev, T, D, iters=20):
     """The gated residual + LayerNorm-Modulate fusion on the workload's shape (bf16, one sample):
     fused forward against the unfused chain (residual kernel, then lnmod_forward on h), and the
     fused backward.  Algorithmic bytes per token: forward 8D+8 (x, u in; h, y, statistics out),
@@ -320,9 +327,9 @@ def _run_gated(lnmod, torch, stream, st, dev, T, D):
                                         dg, dsh, dsc, ws, ws.numel(), BF)
         assert rc == 0, lnmod.lnmod_status_string(rc)
 
-    f_ms = _time_ms(torch, stream, fused_fwd)
-    uf_ms = _time_ms(torch, stream, unfused_fwd)
-    b_ms = _time_ms(torch, stream, fused_bwd)
+    f_ms = _time_ms(torch, stream, fused_fwd, iters=iters)
+    uf_ms = _time_ms(torch, stream, unfused_fwd, iters=iters)
+    b_ms = _time_ms(torch, stream, fused_bwd, iters=iters)
     fwd_b, bwd_b = T * (8 * D + 8), T * (12 * D + 8)
     return {"workload": "gated residual + LN-Modulate, bf16 B=1 S=%d D=%d" % (T, D),
             "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
