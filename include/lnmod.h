@@ -189,6 +189,39 @@ size_t lnmod_gated_backward_workspace_bytes(int64_t B_or_nseg, int64_t total_tok
 int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t B, int64_t S,
                         int64_t D, void* stream, void* h, int dtype);
 
+/*
+ * Fused Q-Norm + K-Norm: the paper lists it among its fused operators (Sec. 4.4) without defining
+ * it; defined here as the query/key normalisation of MMDiT-style attention blocks, a root-mean-
+ * square normalisation with a learned weight, applied to both tensors by one launch:
+ *
+ *     rstd_n = 1/sqrt((1/D) sum_d x[n,d]^2 + eps)     y[n,d] = (x[n,d]*rstd_n) * w[d]
+ *
+ * for (x, w, y, rstd) = (q, wq, q_out, rstd_q) and (k, wk, k_out, rstd_k).  q, k, q_out, k_out:
+ * [N, D] in the I/O dtype; wq, wk: [D] in the I/O dtype; rstd_q, rstd_k: float32 [N] (written).
+ * N is the number of rows normalised (tokens, or tokens x heads when D is one head's width).
+ * Errors as for lnmod_forward.
+ */
+int lnmod_qknorm_forward(const void* q, const void* k, const void* wq, const void* wk,
+                         int64_t N, int64_t D, float eps, void* stream,
+                         void* q_out, void* k_out, float* rstd_q, float* rstd_k, int dtype);
+
+/*
+ * Backward of the above, per tensor:  g = dy*w,  c_n = (1/D) sum_d g*xhat,
+ * dx = rstd_n*(g - xhat*c_n),  dw[d] = sum_n dy[n,d]*xhat[n,d]  (xhat = x*rstd_n).
+ * dq_out, dk_out: gradients of q_out, k_out; rstd_q, rstd_k: what the forward saved; dq, dk:
+ * [N, D] in the I/O dtype; dwq, dwk: float32 [D], sums over all N rows in a fixed order (zeros
+ * when N == 0).  workspace: lnmod_qknorm_backward_workspace_bytes(N, D) bytes, contents need no
+ * initialisation.  `eps` is only validated.  Errors as for lnmod_backward.
+ */
+int lnmod_qknorm_backward(const void* dq_out, const void* dk_out, const void* q, const void* k,
+                          const void* wq, const void* wk, int64_t N, int64_t D, float eps,
+                          void* stream, const float* rstd_q, const float* rstd_k,
+                          void* dq, void* dk, float* dwq, float* dwk,
+                          void* workspace, size_t workspace_bytes, int dtype);
+
+/* Bytes of device workspace lnmod_qknorm_backward needs (0 for invalid arguments).  Host-only. */
+size_t lnmod_qknorm_backward_workspace_bytes(int64_t N, int64_t D);
+
 #ifdef __cplusplus
 }
 #endif

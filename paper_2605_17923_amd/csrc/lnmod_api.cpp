@@ -108,6 +108,16 @@ size_t gated_workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
     return static_cast<size_t>(slots) * 3u * static_cast<size_t>(D) * sizeof(float);
 }
 
+size_t qknorm_workspace_bytes(int64_t N, int64_t D) {
+    int64_t nb = 0;
+    for (int dtype = 0; dtype < 2; ++dtype) {
+        if (D % (dtype == 0 ? 8 : 4) != 0) continue;
+        const int64_t b = lnmod::qknorm_bwd_blocks(N, D, dtype);
+        if (b > nb) nb = b;
+    }
+    return static_cast<size_t>(2 * nb) * static_cast<size_t>(D) * sizeof(float);
+}
+
 // (segments, tokens per sample, total tokens) of a gated call, or false on overflow
 bool gated_shape(const int32_t* cu, int64_t B_or_nseg, int64_t S_or_T, int64_t* S, int64_t* T) {
     if (cu) {
@@ -272,6 +282,53 @@ int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t 
     const Problem p{dtype, nullptr, B, S, T, D, 1.0f};
     const hipError_t e = lnmod::launch_gate_residual(p, x, u, gate, h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_qknorm_forward(const void* q, const void* k, const void* wq, const void* wk, int64_t N,
+                         int64_t D, float eps, void* stream, void* q_out, void* k_out,
+                         float* rstd_q, float* rstd_k, int dtype) {
+    const int st = check_shape(1, N, D, eps, dtype, N);
+    if (st != LNMOD_OK) return st;
+    if (N == 0) return LNMOD_OK;
+    if (!q || !k || !wq || !wk || !q_out || !k_out || !rstd_q || !rstd_k) return LNMOD_EINVAL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(wq) || !aligned16(wk) || !aligned16(q_out) ||
+        !aligned16(k_out))
+        return LNMOD_EALIGN;
+    const hipError_t e = lnmod::launch_qknorm_fwd(dtype, q, k, wq, wk, N, D, eps, q_out, k_out, rstd_q,
+                                                  rstd_k, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_qknorm_backward(const void* dq_out, const void* dk_out, const void* q, const void* k,
+                          const void* wq, const void* wk, int64_t N, int64_t D, float eps,
+                          void* stream, const float* rstd_q, const float* rstd_k, void* dq, void* dk,
+                          float* dwq, float* dwk, void* workspace, size_t workspace_size, int dtype) {
+    const int st = check_shape(1, N, D, eps, dtype, N);
+    if (st != LNMOD_OK) return st;
+    const hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (N == 0) {                                             // empty sums are zeros
+        if (!dwq || !dwk) return LNMOD_EINVAL;
+        hipError_t e = lnmod::launch_zero_f32(dwq, D, hs);
+        if (e == hipSuccess) e = lnmod::launch_zero_f32(dwk, D, hs);
+        return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+    }
+    if (!dq_out || !dk_out || !q || !k || !wq || !wk || !rstd_q || !rstd_k || !dq || !dk || !dwq || !dwk)
+        return LNMOD_EINVAL;
+    if (!aligned16(dq_out) || !aligned16(dk_out) || !aligned16(q) || !aligned16(k) || !aligned16(wq) ||
+        !aligned16(wk) || !aligned16(dq) || !aligned16(dk))
+        return LNMOD_EALIGN;
+    if (!workspace || workspace_size < qknorm_workspace_bytes(N, D)) return LNMOD_EWORKSPACE;
+    if (!aligned16(workspace)) return LNMOD_EALIGN;
+    const hipError_t e = lnmod::launch_qknorm_bwd(dtype, dq_out, dk_out, q, k, wq, wk, N, D, rstd_q,
+                                                  rstd_k, dq, dk, dwq, dwk,
+                                                  static_cast<float*>(workspace), hs);
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+size_t lnmod_qknorm_backward_workspace_bytes(int64_t N, int64_t D) {
+    if (N < 0 || N >= (int64_t(1) << 31)) return 0;
+    if (D < 8 || D > lnmod::kMaxD || D % 4 != 0) return 0;
+    return qknorm_workspace_bytes(N, D);
 }
 
 int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream) {

@@ -129,4 +129,15 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
                             float* dscale, float* ws, hipStream_t st);
 hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t st);
 
+
+// Fused Q-Norm + K-Norm (RMS normalisation with a learned weight of two tensors, one launch).
+int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype);      // partial-sum slots per tensor
+hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void* wq, const void* wk,
+                             int64_t N, int64_t D, float eps, void* q_out, void* k_out,
+                             float* rstd_q, float* rstd_k, hipStream_t st);
+hipError_t launch_qknorm_bwd(int dtype, const void* dq_out, const void* dk_out, const void* q,
+                             const void* k, const void* wq, const void* wk, int64_t N, int64_t D,
+                             const float* rstd_q, const float* rstd_k, void* dq, void* dk,
+                             float* dwq, float* dwk, float* ws, hipStream_t st);
+
 }  // namespace lnmod

@@ -1,0 +1,152 @@
+// lnmod_qknorm.hip -- instantiation and launch of the fused Q-Norm + K-Norm kernels (forward,
+// backward and the fixed-order second pass of the weight gradients).
+#include "lnmod_qknorm_kernels.hpp"
+#include "lnmod_launch.hpp"
+
+namespace lnmod {
+namespace {
+
+constexpr int kRows = 2;           // rows per block and step
+
+// Resident blocks per CU over both tensors together; each tensor gets half of them.
+int fwd_blocks_per_cu(int K) {
+    if (K == 1) return 4;
+    const int b = 5 / K;
+    return b < 1 ? 1 : b;
+}
+int bwd_blocks_per_cu(int K) {
+    if (K == 1) return 4;
+    const int b = 6 / K;
+    return b < 1 ? 1 : b;
+}
+
+int32_t blocks_per_tensor(int64_t N, int per_cu) {
+    int64_t nb = static_cast<int64_t>(kNumCU) * per_cu / 2;
+    const int64_t need = (N + kRows - 1) / kRows;
+    if (nb > need) nb = need;
+    return static_cast<int32_t>(nb < 1 ? 1 : nb);
+}
+
+template <typename Tag, int VPL, int K>
+void go_fwd(const QkFwdArgs& a, hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>(2 * a.nb)), block(K * kWave);
+    if (a.nchunks == K * VPL * kWave)
+        hipLaunchKernelGGL((qknorm_fwd_kernel<Tag, VPL, K, kRows, true>), grid, block, 0, st, a);
+    else
+        hipLaunchKernelGGL((qknorm_fwd_kernel<Tag, VPL, K, kRows, false>), grid, block, 0, st, a);
+}
+
+template <typename Tag, int VPL, int K>
+void go_bwd(const QkBwdArgs& a, hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>(2 * a.nb)), block(K * kWave);
+    if (a.nchunks == K * VPL * kWave)
+        hipLaunchKernelGGL((qknorm_bwd_kernel<Tag, VPL, K, kRows, true>), grid, block, 0, st, a);
+    else
+        hipLaunchKernelGGL((qknorm_bwd_kernel<Tag, VPL, K, kRows, false>), grid, block, 0, st, a);
+}
+
+// calls f.template operator()<VPL, K>() for the split; VPL_WIDE as in the other launchers
+template <typename Tag, int VPL_WIDE, typename F>
+void for_split(Split sp, F&& f) {
+    if (sp.K == 1) {
+        switch (sp.VPL) {
+            case 1: f.template operator()<1, 1>(); break;
+            case 2: f.template operator()<2, 1>(); break;
+            case 3: f.template operator()<3, 1>(); break;
+            default:                             // 4 and 6 chunks per lane: fp32 rows only
+                if constexpr (IO<Tag>::E == 4) {
+                    if (sp.VPL == 4) f.template operator()<4, 1>();
+                    else f.template operator()<6, 1>();
+                }
+                break;
+        }
+        return;
+    }
+    switch (sp.K) {
+        case 2: f.template operator()<VPL_WIDE, 2>(); break;
+        case 3: f.template operator()<VPL_WIDE, 3>(); break;
+        case 4: f.template operator()<VPL_WIDE, 4>(); break;
+        case 5: f.template operator()<VPL_WIDE, 5>(); break;
+        case 6: f.template operator()<VPL_WIDE, 6>(); break;
+        default: f.template operator()<VPL_WIDE, 8>(); break;
+    }
+}
+
+template <typename Tag>
+struct FwdGo {
+    const QkFwdArgs& a;
+    hipStream_t st;
+    template <int VPL, int K> void operator()() const { go_fwd<Tag, VPL, K>(a, st); }
+};
+template <typename Tag>
+struct BwdGo {
+    const QkBwdArgs& a;
+    hipStream_t st;
+    template <int VPL, int K> void operator()() const { go_bwd<Tag, VPL, K>(a, st); }
+};
+
+}  // namespace
+
+int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype) {
+    const int E = dtype == 0 ? 8 : 4;
+    const Split sp = choose_split(static_cast<int>(D / E), dtype);
+    return blocks_per_tensor(N, bwd_blocks_per_cu(sp.K));
+}
+
+hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void* wq, const void* wk,
+                             int64_t N, int64_t D, float eps, void* q_out, void* k_out,
+                             float* rstd_q, float* rstd_k, hipStream_t st) {
+    const int E = dtype == 0 ? 8 : 4;
+    QkFwdArgs a;
+    a.x[0] = q; a.x[1] = k;
+    a.w[0] = wq; a.w[1] = wk;
+    a.y[0] = q_out; a.y[1] = k_out;
+    a.rstd[0] = rstd_q; a.rstd[1] = rstd_k;
+    a.N = N;
+    a.D = static_cast<int32_t>(D);
+    a.nchunks = static_cast<int32_t>(D / E);
+    a.eps = eps;
+    a.inv_D = 1.0f / static_cast<float>(D);
+    const Split sp = choose_split(a.nchunks, dtype);
+    a.nb = blocks_per_tensor(N, fwd_blocks_per_cu(sp.K));
+    if (dtype == 0) for_split<bf16_io, 2>(sp, FwdGo<bf16_io>{a, st});
+    else for_split<f32_io, 4>(sp, FwdGo<f32_io>{a, st});
+    return hipGetLastError();
+}
+
+hipError_t launch_qknorm_bwd(int dtype, const void* dq_out, const void* dk_out, const void* q,
+                             const void* k, const void* wq, const void* wk, int64_t N, int64_t D,
+                             const float* rstd_q, const float* rstd_k, void* dq, void* dk,
+                             float* dwq, float* dwk, float* ws, hipStream_t st) {
+    const int E = dtype == 0 ? 8 : 4;
+    QkBwdArgs a;
+    a.dy[0] = dq_out; a.dy[1] = dk_out;
+    a.x[0] = q; a.x[1] = k;
+    a.w[0] = wq; a.w[1] = wk;
+    a.rstd[0] = rstd_q; a.rstd[1] = rstd_k;
+    a.dx[0] = dq; a.dx[1] = dk;
+    a.ws = ws;
+    a.N = N;
+    a.D = static_cast<int32_t>(D);
+    a.nchunks = static_cast<int32_t>(D / E);
+    a.inv_D = 1.0f / static_cast<float>(D);
+    const Split sp = choose_split(a.nchunks, dtype);
+    a.nb = qknorm_bwd_blocks(N, D, dtype);
+    if (dtype == 0) for_split<bf16_io, 2>(sp, BwdGo<bf16_io>{a, st});
+    else for_split<f32_io, 4>(sp, BwdGo<f32_io>{a, st});
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    QkReduceArgs r;
+    r.ws = ws;
+    r.dw[0] = dwq;
+    r.dw[1] = dwk;
+    r.nb = a.nb;
+    r.D = a.D;
+    r.dblocks = static_cast<int32_t>((D + kWave - 1) / kWave);
+    hipLaunchKernelGGL(qknorm_reduce_kernel<0>, dim3(static_cast<unsigned>(2 * r.dblocks)),
+                       dim3(kReduceWaves * kWave), 0, st, r);
+    return hipGetLastError();
+}
+
+}  // namespace lnmod

@@ -22,7 +22,8 @@ LIBRARY = os.path.join(_HERE, "liblnmod.so")
 EXPORTS = ("lnmod_forward", "lnmod_backward", "lnmod_forward_varlen", "lnmod_backward_varlen",
            "lnmod_backward_workspace_bytes", "lnmod_status_string", "lnmod_unfused_forward",
            "lnmod_copy", "lnmod_gated_forward", "lnmod_gated_backward",
-           "lnmod_gated_backward_workspace_bytes", "lnmod_gate_residual")
+           "lnmod_gated_backward_workspace_bytes", "lnmod_gate_residual", "lnmod_qknorm_forward",
+           "lnmod_qknorm_backward", "lnmod_qknorm_backward_workspace_bytes")
 
 _lib = None
 
@@ -72,6 +73,13 @@ def library() -> ctypes.CDLL:
     lib.lnmod_gated_backward_workspace_bytes.argtypes = [i64, i64, i64]
     lib.lnmod_gate_residual.restype = cint
     lib.lnmod_gate_residual.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, cint]
+    lib.lnmod_qknorm_forward.restype = cint
+    lib.lnmod_qknorm_forward.argtypes = [vp, vp, vp, vp, i64, i64, f32, vp, vp, vp, vp, vp, cint]
+    lib.lnmod_qknorm_backward.restype = cint
+    lib.lnmod_qknorm_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, f32, vp, vp, vp,
+                                          vp, vp, vp, vp, vp, sz, cint]
+    lib.lnmod_qknorm_backward_workspace_bytes.restype = sz
+    lib.lnmod_qknorm_backward_workspace_bytes.argtypes = [i64, i64]
     _lib = lib
     return lib
 
@@ -160,6 +168,23 @@ def lnmod_gated_backward_workspace_bytes(B_or_nseg, total_tokens, D):
 
 def lnmod_gate_residual(x, u, gate, B, S, D, stream, h, dtype):
     return library().lnmod_gate_residual(_p(x), _p(u), _p(gate), B, S, D, stream, _p(h), dtype)
+
+
+def lnmod_qknorm_forward(q, k, wq, wk, N, D, eps, stream, q_out, k_out, rstd_q, rstd_k, dtype):
+    return library().lnmod_qknorm_forward(_p(q), _p(k), _p(wq), _p(wk), N, D, eps, stream,
+                                          _p(q_out), _p(k_out), _p(rstd_q), _p(rstd_k), dtype)
+
+
+def lnmod_qknorm_backward(dq_out, dk_out, q, k, wq, wk, N, D, eps, stream, rstd_q, rstd_k, dq, dk,
+                          dwq, dwk, workspace, workspace_bytes, dtype):
+    return library().lnmod_qknorm_backward(_p(dq_out), _p(dk_out), _p(q), _p(k), _p(wq), _p(wk),
+                                           N, D, eps, stream, _p(rstd_q), _p(rstd_k), _p(dq),
+                                           _p(dk), _p(dwq), _p(dwk), _p(workspace),
+                                           workspace_bytes, dtype)
+
+
+def lnmod_qknorm_backward_workspace_bytes(N, D):
+    return int(library().lnmod_qknorm_backward_workspace_bytes(N, D))
 
 
 # ---- conveniences: allocate outputs with torch, raise on a non-zero status ----------------------
@@ -290,3 +315,34 @@ def gated_backward(dy, dh, h, u, gate, scale, mean, rstd, cu_seqlens=None, eps=1
                                 _stream_handle(stream), mean, rstd, dx, du, dgate, dshift, dscale,
                                 ws, ws.numel(), _dtype_code(h)), "lnmod_gated_backward")
     return dx, du, dgate, dshift, dscale
+
+
+def qknorm_forward(q, k, wq, wk, eps=1e-6, stream=None):
+    """RMS normalisation with weight of q and k ([..., D], same shape) in one launch
+    -> q_out, k_out, rstd_q, rstd_k (float32, one per row)."""
+    import torch
+    D = q.shape[-1]
+    N = q.numel() // D
+    q_out, k_out = torch.empty_like(q), torch.empty_like(k)
+    rq = torch.empty(N, dtype=torch.float32, device=q.device)
+    rk = torch.empty(N, dtype=torch.float32, device=q.device)
+    _check(lnmod_qknorm_forward(q, k, wq, wk, N, D, eps, _stream_handle(stream), q_out, k_out, rq, rk,
+                                _dtype_code(q)), "lnmod_qknorm_forward")
+    return q_out, k_out, rq, rk
+
+
+def qknorm_backward(dq_out, dk_out, q, k, wq, wk, rstd_q, rstd_k, eps=1e-6, stream=None, ws=None):
+    """-> dq, dk (I/O dtype) and dwq, dwk (float32 [D])."""
+    import torch
+    D = q.shape[-1]
+    N = q.numel() // D
+    dq, dk = torch.empty_like(q), torch.empty_like(k)
+    dwq = torch.empty(D, dtype=torch.float32, device=q.device)
+    dwk = torch.empty(D, dtype=torch.float32, device=q.device)
+    if ws is None:
+        ws = torch.empty(max(lnmod_qknorm_backward_workspace_bytes(N, D), 16), dtype=torch.uint8,
+                         device=q.device)
+    _check(lnmod_qknorm_backward(dq_out, dk_out, q, k, wq, wk, N, D, eps, _stream_handle(stream),
+                                 rstd_q, rstd_k, dq, dk, dwq, dwk, ws, ws.numel(), _dtype_code(q)),
+           "lnmod_qknorm_backward")
+    return dq, dk, dwq, dwk

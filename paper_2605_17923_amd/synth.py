@@ -188,3 +188,37 @@ def make_gated_extras(inp: Inputs, seed: int) -> GatedExtras:
     if inp.workload.dtype == "bf16":
         u, gate, dh = round_to_bf16(u), round_to_bf16(gate), round_to_bf16(dh)
     return GatedExtras(u, gate, dh)
+
+
+@dataclass
+class QkNormInputs:
+    """Inputs of the fused Q-Norm + K-Norm operator: float32 host arrays, exact in `dtype`."""
+    q: np.ndarray                   # [N, D]
+    k: np.ndarray
+    wq: np.ndarray                  # [D]
+    wk: np.ndarray
+    dq_out: np.ndarray              # [N, D] gradients of the normalised tensors
+    dk_out: np.ndarray
+    dtype: str
+    eps: float = 1e-6
+
+
+def make_qknorm_inputs(N: int, D: int, dtype: str = "bf16", seed: int = 0,
+                       outlier_p: float = 1e-3) -> QkNormInputs:
+    """q ~ N(0, 1) and k ~ N(0.2, 2) with a Bernoulli(outlier_p) mask of entries multiplied by 30
+    (projection outputs have heavy tails), weights ~ N(1, 0.1), upstream gradients ~ N(0, 1)."""
+    rng = np.random.default_rng(seed)
+    q = _normal(rng, (N, D), 0.0, 1.0)
+    k = _normal(rng, (N, D), 0.2, 2.0)
+    if outlier_p > 0.0 and N > 0:
+        for a in (q, k):
+            mask = rng.random((N, D), dtype=np.float32) < np.float32(outlier_p)
+            a[mask] *= np.float32(30.0)
+    wq, wk = _normal(rng, (D,), 1.0, 0.1), _normal(rng, (D,), 1.0, 0.1)
+    dq, dk = _normal(rng, (N, D), 0.0, 1.0), _normal(rng, (N, D), 0.0, 1.0)
+    arrs = [q, k, wq, wk, dq, dk]
+    if dtype == "bf16":
+        arrs = [round_to_bf16(a) for a in arrs]
+    elif dtype != "f32":
+        raise ValueError("dtype must be 'bf16' or 'f32'")
+    return QkNormInputs(*arrs, dtype=dtype)

@@ -190,6 +190,28 @@ def test_gated_workspace_query(lib):
     assert m % slot == 0 and m >= 24 * slot
 
 
+def test_qknorm_rejects_bad_arguments_and_sizes_workspace(lib):
+    E = lnmod
+    f = lambda q=A, k=A, wq=A, wk=A, N=10, D=64, eps=1e-6, qo=A, ko=A, rq=A, rk=A, dtype=0: \
+        lnmod.lnmod_qknorm_forward(q, k, wq, wk, N, D, eps, None, qo, ko, rq, rk, dtype)
+    assert f(k=None) == E.LNMOD_EINVAL and f(rk=None) == E.LNMOD_EINVAL and f(eps=-1.0) == E.LNMOD_EINVAL
+    assert f(N=-1) == E.LNMOD_EINVAL and f(N=1 << 31) == E.LNMOD_EINVAL and f(dtype=5) == E.LNMOD_EINVAL
+    assert f(D=12) == E.LNMOD_EUNSUPPORTED and f(D=8200) == E.LNMOD_EUNSUPPORTED
+    assert f(wq=A + 8) == E.LNMOD_EALIGN and f(ko=A + 2) == E.LNMOD_EALIGN
+    assert f(N=0) == E.LNMOD_OK
+    b = lambda dqo=A, dko=A, q=A, k=A, wq=A, wk=A, N=10, D=64, eps=1e-6, rq=A, rk=A, dq=A, dk=A, dwq=A, \
+        dwk=A, ws=A, wsb=1 << 40, dtype=0: lnmod.lnmod_qknorm_backward(
+            dqo, dko, q, k, wq, wk, N, D, eps, None, rq, rk, dq, dk, dwq, dwk, ws, wsb, dtype)
+    assert b(dko=None) == E.LNMOD_EINVAL and b(dwk=None) == E.LNMOD_EINVAL
+    assert b(D=68) == E.LNMOD_EUNSUPPORTED and b(dq=A + 4) == E.LNMOD_EALIGN
+    assert b(ws=None) == E.LNMOD_EWORKSPACE and b(wsb=8) == E.LNMOD_EWORKSPACE and b(ws=A + 4) == E.LNMOD_EALIGN
+    wq = lnmod.lnmod_qknorm_backward_workspace_bytes
+    assert wq(-1, 64) == 0 and wq(10, 66) == 0
+    n = wq(75600, 5120)
+    assert n % (2 * 5120 * 4) == 0 and 0 < 2 * n <= 0.05 * 2 * 75600 * 6 * 5120
+    assert wq(1, 5120) == 2 * 5120 * 4
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(lnmod, "_lib", None)
     monkeypatch.setattr(lnmod, "LIBRARY", os.path.join(tmp_path, "nope.so"))

@@ -1,0 +1,104 @@
+"""GPU parity of the fused Q-Norm + K-Norm kernels (called through the C ABI) against the float64
+oracle in oracle/qknorm_oracle.c on the same seeded inputs, with the tolerances of the
+LayerNorm-Modulate tests (bf16 tensors: rel-L2 4e-3 and one bf16 rounding; fp32 tensors and the
+float32 weight gradients: 1e-5; rstd: 1e-5 relative)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qknorm_oracle as qo
+from paper_2605_17923_amd import lnmod, synth
+from parity_util import check_f32_tensor, check_io_tensor, to_device, to_host64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lnmod.library()
+    yield
+    torch.cuda.synchronize()
+
+
+def run_qk(inp, sample_rows=None, label=""):
+    dt = inp.dtype
+    N, D = inp.q.shape
+    print("qknorm case", label, "dtype", dt, "N", N, "D", D, flush=True)
+    q, k, wq, wk, dqo, dko = (to_device(a, dt) for a in (inp.q, inp.k, inp.wq, inp.wk, inp.dq_out, inp.dk_out))
+    q_out, k_out, rq, rk = lnmod.qknorm_forward(q, k, wq, wk, inp.eps)
+    dq, dk, dwq, dwk = lnmod.qknorm_backward(dqo, dko, q, k, wq, wk, rq, rk, inp.eps)
+    torch.cuda.synchronize()
+    rows = np.arange(N) if sample_rows is None else np.asarray(sample_rows, dtype=np.int64)
+    rows_t = torch.from_numpy(rows).cuda()
+    for name, x, w, dy, y_g, r_g, dx_g, dw_g in (("q", inp.q, inp.wq, inp.dq_out, q_out, rq, dq, dwq),
+                                                 ("k", inp.k, inp.wk, inp.dk_out, k_out, rk, dk, dwk)):
+        y64, r64 = qo.forward_one(x[rows], w, inp.eps)              # rows are independent in the forward
+        check_io_tensor(name + "_out", y_g[rows_t], y64, dt)
+        rel = np.abs(to_host64(r_g[rows_t]) - r64) / r64
+        assert rel.max() <= 1e-5, "rstd_%s: relative error %.3e" % (name, rel.max())
+        dx64, dw64 = qo.backward_one(dy, x, w, inp.eps)
+        check_io_tensor("d" + name, dx_g[rows_t], dx64[rows], dt)
+        check_f32_tensor("dw" + name, dw_g, dw64)
+
+
+def test_qknorm_bf16_d5120():
+    run_qk(synth.make_qknorm_inputs(1031, 5120, "bf16", 3001))
+
+
+def test_qknorm_bf16_d1536():
+    run_qk(synth.make_qknorm_inputs(2311, 1536, "bf16", 3002))
+
+
+def test_qknorm_fp32_d1536():
+    run_qk(synth.make_qknorm_inputs(512, 1536, "f32", 3003))
+
+
+@pytest.mark.parametrize("D,dtype", [(8, "bf16"), (128, "bf16"), (200, "bf16"), (1528, "bf16"), (2560, "bf16"),
+                                     (3072, "bf16"), (8192, "bf16"), (100, "f32"),
+                                     (128, "f32"), (1100, "f32"), (5120, "f32"), (8192, "f32")])
+def test_qknorm_hidden_sizes(D, dtype):
+    run_qk(synth.make_qknorm_inputs(131, D, dtype, 3100 + D), label="D=%d %s" % (D, dtype))
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 255, 257, 513])
+def test_qknorm_row_counts(N):
+    run_qk(synth.make_qknorm_inputs(N, 1024, "bf16", 3200 + N), label="N=%d" % N)
+
+
+def test_qknorm_per_head_view():
+    # one head's width as the normalised dimension: [tokens*heads, 128]
+    run_qk(synth.make_qknorm_inputs(300 * 40, 128, "bf16", 3004), label="per head")
+
+
+def test_qknorm_zero_rows_and_zero_inputs():
+    inp = synth.make_qknorm_inputs(64, 512, "bf16", 3005)
+    inp.q[3, :] = 0.0                       # rstd = 1/sqrt(eps), y = 0, dx = rstd * dy * w
+    inp.k[:] = 0.0
+    run_qk(inp, label="zero rows")
+
+
+def test_qknorm_empty_and_repeatable():
+    D = 512
+    z = torch.empty(0, D, dtype=torch.bfloat16, device="cuda")
+    w = torch.ones(D, dtype=torch.bfloat16, device="cuda")
+    q_out, k_out, rq, rk = lnmod.qknorm_forward(z, z, w, w)
+    dq, dk, dwq, dwk = lnmod.qknorm_backward(z, z, z, z, w, w, rq, rk)
+    torch.cuda.synchronize()
+    assert q_out.shape == (0, D) and torch.all(dwq == 0) and torch.all(dwk == 0)
+    inp = synth.make_qknorm_inputs(777, 5120, "bf16", 3006)
+    dev = [to_device(a, "bf16") for a in (inp.q, inp.k, inp.wq, inp.wk, inp.dq_out, inp.dk_out)]
+    outs = []
+    for _ in range(2):
+        f = lnmod.qknorm_forward(*dev[:4])
+        outs.append(f + lnmod.qknorm_backward(dev[4], dev[5], dev[0], dev[1], dev[2], dev[3], f[2], f[3]))
+    torch.cuda.synchronize()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_qknorm_full_size():
+    inp = synth.make_qknorm_inputs(75600, 5120, "bf16", 3007)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.integers(0, 75600, 1000), [0, 1, 2, 75597, 75598, 75599]]))
+    run_qk(inp, sample_rows=rows, label="full size")
