@@ -102,8 +102,9 @@ def main():
                     help="only run lnmod_copy on a buffer of the workload's size (a kernel of known "
                          "traffic for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--gated-only", action="store_true",
-                    help="only time the gated residual + LayerNorm-Modulate fusion on the workload's "
-                         "shape (for profiling its kernels; not the headline metric)")
+                    help="only time the gated residual + LayerNorm-Modulate and the Q-Norm + K-Norm "
+                         "fusions on the workload's shape (for profiling their kernels; not the "
+                         "headline metric)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the copy ceiling, the unfused comparison and the D=1536 forward")
     args = ap.parse_args()
@@ -132,7 +133,9 @@ def main():
         return
     if args.gated_only:
         stream = torch.cuda.current_stream()
-        print(json.dumps(_run_gated(lnmod, torch, stream, stream.cuda_stream, dev, T, D, iters=args.steps)))
+        print(json.dumps({"gated": _run_gated(lnmod, torch, stream, stream.cuda_stream, dev, T, D, iters=args.steps),
+                          "qknorm": _run_qknorm(lnmod, torch, stream, stream.cuda_stream, dev, T, D,
+                                                iters=args.steps)}))
         return
     x, dy, shift, scale = make_device_inputs(T, D, 1003, dev)
     y, dx = torch.empty_like(x), torch.empty_like(x)
@@ -337,6 +340,37 @@ def _run_gated(lnmod, torch, stream, st, dev, T, D, iters=20):
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
 
 
+def _run_qknorm(lnmod, torch, stream, st, dev, T, D, iters=20):
+    """The fused Q-Norm + K-Norm on the workload's shape (bf16): both tensors in one launch.
+    Algorithmic bytes per token: forward 8D+8 (q, k in; both out; two rstd), backward 12D+8."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(78)
+    q, k, dqo, dko = (_randn_bf16(torch, g, (T, D), dev) for _ in range(4))
+    wq, wk = (_randn_bf16(torch, g, (D,), dev, 0.1, 1.0) for _ in range(2))
+    q_out, k_out, dq, dk = (torch.empty_like(q) for _ in range(4))
+    rq = torch.empty(T, dtype=torch.float32, device=dev)
+    rk = torch.empty(T, dtype=torch.float32, device=dev)
+    dwq, dwk = (torch.empty(D, dtype=torch.float32, device=dev) for _ in range(2))
+    ws = torch.empty(max(lnmod.lnmod_qknorm_backward_workspace_bytes(T, D), 16), dtype=torch.uint8, device=dev)
+    BF = lnmod.LNMOD_BF16
+
+    def fwd():
+        rc = lnmod.lnmod_qknorm_forward(q, k, wq, wk, T, D, 1e-6, st, q_out, k_out, rq, rk, BF)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    def bwd():
+        rc = lnmod.lnmod_qknorm_backward(dqo, dko, q, k, wq, wk, T, D, 1e-6, st, rq, rk, dq, dk, dwq, dwk,
+                                         ws, ws.numel(), BF)
+        assert rc == 0, lnmod.lnmod_status_string(rc)
+
+    f_ms = _time_ms(torch, stream, fwd, iters=iters)
+    b_ms = _time_ms(torch, stream, bwd, iters=iters)
+    fwd_b, bwd_b = T * (8 * D + 8), T * (12 * D + 8)
+    return {"workload": "Q-Norm + K-Norm, bf16 N=%d D=%d" % (T, D),
+            "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
+            "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
+
+
 def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
     """Context figures: a plain copy as the practical bandwidth ceiling, the unfused two-kernel
     forward (LayerNorm -> xhat in HBM -> modulate), the other workload shapes and the token
@@ -367,6 +401,7 @@ def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused
                       24, 0, 5120, PS, lengths=lengths, seed=1005),
     ]
     res["gated"] = _run_gated(lnmod, torch, stream, st, dev, T, D)
+    res["qknorm"] = _run_qknorm(lnmod, torch, stream, st, dev, T, D)
     grid = []
     for n in range(8000, 64001, 8000):
         r = _run_workload(lnmod, torch, stream, st, dev, "N=%d" % n, 1, n, 5120, PS, seed=n)
