@@ -15,10 +15,10 @@ BUILD_DIR = os.path.join(HERE, "_build")
 LIBRARY = os.path.join(HERE, "liblnmod.so")
 
 SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated_bwd.hip",
-           "lnmod_qknorm.hip", "lnmod_misc.hip", "lnmod_api.cpp"]
+           "lnmod_qknorm.hip", "lnmod_misc.hip", "lnmod_api.cpp", "lnmod_sched.cpp"]
 HEADERS = [os.path.join(CSRC, "lnmod_kernels.hpp"), os.path.join(CSRC, "lnmod_launch.hpp"),
            os.path.join(CSRC, "lnmod_gated_kernels.hpp"), os.path.join(CSRC, "lnmod_qknorm_kernels.hpp"),
-           os.path.join(INCLUDE, "lnmod.h")]
+           os.path.join(INCLUDE, "lnmod.h"), os.path.join(INCLUDE, "lnmod_sched.h")]
 
 # packed-fp32 instructions are switched off on purpose (some of their forms have produced wrong
 # results on these machines); the host pass warns that it does not know the feature
@@ -55,7 +55,7 @@ def _compile(src: str, force: bool) -> str:
 def build_library(force: bool = False, verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link liblnmod.so; returns its path."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIBRARY, objs):
         tmp = LIBRARY + ".tmp.%d" % os.getpid()
