@@ -292,3 +292,45 @@ def test_unfused_comparator_and_copy_match():
     assert lnmod.lnmod_copy(x, dst, x.numel() * 2, s) == lnmod.LNMOD_OK
     torch.cuda.synchronize()
     assert torch.equal(dst, x)
+
+
+def test_calls_can_be_captured_in_a_hip_graph():
+    # the library allocates nothing, never synchronises and records no memset: a forward +
+    # backward pair captured into a HIP graph must replay to the eager results every time, also
+    # after the inputs were changed in place between replays
+    inp = synth.make_inputs(4, lengths=(400, 0, 900, 33), D=5120)
+    T, D, nseg = inp.T, inp.D, inp.B
+    x, dy = to_device(inp.x, "bf16"), to_device(inp.dy, "bf16")
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    mean, rstd = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
+    dsh, dsc = torch.empty(nseg, D, device="cuda"), torch.empty(nseg, D, device="cuda")
+    ws = lnmod.workspace(nseg, T, D, "cuda")
+
+    def launch():
+        s = torch.cuda.current_stream().cuda_stream
+        assert lnmod.lnmod_forward_varlen(x, shift, scale, cu, nseg, T, D, 1e-6, s, y, mean, rstd,
+                                          lnmod.LNMOD_BF16) == lnmod.LNMOD_OK
+        assert lnmod.lnmod_backward_varlen(dy, x, None, scale, cu, nseg, T, D, 1e-6, s, mean, rstd, dx, dsh, dsc,
+                                           ws, ws.numel(), lnmod.LNMOD_BF16) == lnmod.LNMOD_OK
+
+    launch()                                     # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        if rep:
+            x.mul_(-0.5).add_(0.25 * rep)        # new inputs in the same buffers
+            dy.neg_()
+        launch()                                 # eager reference for the current inputs
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (y, mean, rstd, dx, dsh, dsc)]
+        for t in (y, mean, rstd, dx, dsh, dsc):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((y, mean, rstd, dx, dsh, dsc), want):
+            assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
