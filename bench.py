@@ -135,7 +135,9 @@ def main():
         stream = torch.cuda.current_stream()
         print(json.dumps({"gated": _run_gated(lnmod, torch, stream, stream.cuda_stream, dev, T, D, iters=args.steps),
                           "qknorm": _run_qknorm(lnmod, torch, stream, stream.cuda_stream, dev, T, D,
-                                                iters=args.steps)}))
+                                                iters=args.steps),
+                          "qknorm_per_head": _run_qknorm(lnmod, torch, stream, stream.cuda_stream, dev,
+                                                         T * (D // 128), 128, iters=args.steps)}))
         return
     x, dy, shift, scale = make_device_inputs(T, D, 1003, dev)
     y, dx = torch.empty_like(x), torch.empty_like(x)
@@ -402,6 +404,7 @@ def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused
     ]
     res["gated"] = _run_gated(lnmod, torch, stream, st, dev, T, D)
     res["qknorm"] = _run_qknorm(lnmod, torch, stream, st, dev, T, D)
+    res["qknorm_per_head"] = _run_qknorm(lnmod, torch, stream, st, dev, T * (D // 128), 128)
     grid = []
     for n in range(8000, 64001, 8000):
         r = _run_workload(lnmod, torch, stream, st, dev, "N=%d" % n, 1, n, 5120, PS, seed=n)

@@ -85,11 +85,32 @@ struct BwdGo {
     template <int VPL, int K> void operator()() const { go_bwd<Tag, VPL, K>(a, st); }
 };
 
+// Short rows (at most 32 chunks, e.g. one head's width): 16 lanes per row, four rows per wave.
+constexpr int kShortMaxChunks = 32;
+constexpr int kShortBlocksPerCu = 2;                 // blocks of 4 waves, over both tensors
+
+// rows per wave and step = 4 * R: about 8 KB of loads per wave and step
+template <int VPL> constexpr int short_fwd_r() { return VPL == 1 ? 8 : 4; }
+template <int VPL> constexpr int short_bwd_r() { return VPL == 1 ? 4 : 2; }
+
+int32_t short_blocks_per_tensor(int64_t N, int rows_per_piece) {
+    int64_t nb = static_cast<int64_t>(kNumCU) * kShortBlocksPerCu / 2;
+    const int64_t pieces = (N + rows_per_piece - 1) / rows_per_piece;
+    const int64_t need = (pieces + kShortWaves - 1) / kShortWaves;
+    if (nb > need) nb = need;
+    return static_cast<int32_t>(nb < 1 ? 1 : nb);
+}
+
 }  // namespace
 
 int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Split sp = choose_split(static_cast<int>(D / E), dtype);
+    const int nchunks = static_cast<int>(D / E);
+    if (nchunks <= kShortMaxChunks) {                // one slot per wave
+        const int r = nchunks <= 16 ? short_bwd_r<1>() : short_bwd_r<2>();
+        return short_blocks_per_tensor(N, 4 * r) * kShortWaves;
+    }
+    const Split sp = choose_split(nchunks, dtype);
     return blocks_per_tensor(N, bwd_blocks_per_cu(sp.K));
 }
 
@@ -107,6 +128,19 @@ hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void
     a.nchunks = static_cast<int32_t>(D / E);
     a.eps = eps;
     a.inv_D = 1.0f / static_cast<float>(D);
+    if (a.nchunks <= kShortMaxChunks) {
+        const bool one = a.nchunks <= 16;
+        a.nb = short_blocks_per_tensor(N, 4 * (one ? short_fwd_r<1>() : short_fwd_r<2>()));
+        const dim3 grid(static_cast<unsigned>(2 * a.nb)), block(kShortWaves * kWave);
+        if (dtype == 0) {
+            if (one) hipLaunchKernelGGL((qknorm_short_fwd_kernel<bf16_io, 1, short_fwd_r<1>()>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((qknorm_short_fwd_kernel<bf16_io, 2, short_fwd_r<2>()>), grid, block, 0, st, a);
+        } else {
+            if (one) hipLaunchKernelGGL((qknorm_short_fwd_kernel<f32_io, 1, short_fwd_r<1>()>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((qknorm_short_fwd_kernel<f32_io, 2, short_fwd_r<2>()>), grid, block, 0, st, a);
+        }
+        return hipGetLastError();
+    }
     const Split sp = choose_split(a.nchunks, dtype);
     a.nb = blocks_per_tensor(N, fwd_blocks_per_cu(sp.K));
     if (dtype == 0) for_split<bf16_io, 2>(sp, FwdGo<bf16_io>{a, st});
@@ -130,10 +164,24 @@ hipError_t launch_qknorm_bwd(int dtype, const void* dq_out, const void* dk_out, 
     a.D = static_cast<int32_t>(D);
     a.nchunks = static_cast<int32_t>(D / E);
     a.inv_D = 1.0f / static_cast<float>(D);
-    const Split sp = choose_split(a.nchunks, dtype);
-    a.nb = qknorm_bwd_blocks(N, D, dtype);
-    if (dtype == 0) for_split<bf16_io, 2>(sp, BwdGo<bf16_io>{a, st});
-    else for_split<f32_io, 4>(sp, BwdGo<f32_io>{a, st});
+    int32_t slots = qknorm_bwd_blocks(N, D, dtype);              // per tensor
+    if (a.nchunks <= kShortMaxChunks) {
+        const bool one = a.nchunks <= 16;
+        a.nb = slots / kShortWaves;
+        const dim3 grid(static_cast<unsigned>(2 * a.nb)), block(kShortWaves * kWave);
+        if (dtype == 0) {
+            if (one) hipLaunchKernelGGL((qknorm_short_bwd_kernel<bf16_io, 1, short_bwd_r<1>()>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((qknorm_short_bwd_kernel<bf16_io, 2, short_bwd_r<2>()>), grid, block, 0, st, a);
+        } else {
+            if (one) hipLaunchKernelGGL((qknorm_short_bwd_kernel<f32_io, 1, short_bwd_r<1>()>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((qknorm_short_bwd_kernel<f32_io, 2, short_bwd_r<2>()>), grid, block, 0, st, a);
+        }
+    } else {
+        const Split sp = choose_split(a.nchunks, dtype);
+        a.nb = slots;
+        if (dtype == 0) for_split<bf16_io, 2>(sp, BwdGo<bf16_io>{a, st});
+        else for_split<f32_io, 4>(sp, BwdGo<f32_io>{a, st});
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -141,7 +189,7 @@ hipError_t launch_qknorm_bwd(int dtype, const void* dq_out, const void* dk_out, 
     r.ws = ws;
     r.dw[0] = dwq;
     r.dw[1] = dwk;
-    r.nb = a.nb;
+    r.nb = slots;
     r.D = a.D;
     r.dblocks = static_cast<int32_t>((D + kWave - 1) / kWave);
     hipLaunchKernelGGL(qknorm_reduce_kernel<0>, dim3(static_cast<unsigned>(2 * r.dblocks)),

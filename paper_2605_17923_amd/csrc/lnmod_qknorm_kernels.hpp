@@ -325,6 +325,237 @@ void qknorm_bwd_kernel(const QkBwdArgs a) {
     }
 }
 
+// =============================================================================================
+// Short rows (one head's width as the normalised dimension): a row of at most 16*VPL chunks is
+// held by 16 lanes, so a wave works on four consecutive rows at once and reduces inside each
+// group of 16 lanes with the DPP steps alone (no cross-row step, no LDS, no barrier).  A wave
+// takes R such groups of four rows per step (consecutive rows, so its loads are contiguous), the
+// waves of a tensor's half of the grid take consecutive pieces, and the next piece is requested
+// before the current one is computed.
+// =============================================================================================
+__device__ inline float row16_sum(float v) {
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror
+    return v;                // every lane of the 16 holds the sum of its group
+}
+
+constexpr int kShortWaves = 4;               // waves per block (independent of each other)
+
+template <typename Tag, int VPL, int R>
+__global__ __launch_bounds__(kShortWaves* kWave)
+void qknorm_short_fwd_kernel(const QkFwdArgs a) {
+    using io = IO<Tag>;
+    constexpr int E = io::E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int group = lane >> 4, gl = lane & 15;
+    const uint32_t row_bytes = static_cast<uint32_t>(a.D) * io::kBytes;
+    const int t = blockIdx.x >= static_cast<unsigned>(a.nb) ? 1 : 0;
+    const int64_t member = static_cast<int64_t>(blockIdx.x) - static_cast<int64_t>(t) * a.nb;
+    const char* x = static_cast<const char*>(t ? a.x[1] : a.x[0]);
+    const void* wgt = t ? a.w[1] : a.w[0];
+    char* y = static_cast<char*>(t ? a.y[1] : a.y[0]);
+    float* rstd = t ? a.rstd[1] : a.rstd[0];
+
+    bool ok[VPL];
+    uint32_t off[VPL];
+    float W[VPL][E];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int chunk = i * 16 + gl;
+        ok[i] = chunk < a.nchunks;
+        off[i] = static_cast<uint32_t>(chunk) * 16u;
+        u32x4 rw = u32x4{0u, 0u, 0u, 0u};
+        if (ok[i]) rw = load16_cached(wgt, 0, off[i]);
+        io::unpack(rw, W[i]);
+    }
+
+    constexpr int64_t kPieceRows = 4 * R;                                   // rows per wave and step
+    const int64_t pieces = (a.N + kPieceRows - 1) / kPieceRows;
+    const int64_t stride = static_cast<int64_t>(a.nb) * kShortWaves;
+    auto fetch = [&](int64_t piece, u32x4 (&q)[R][VPL]) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int64_t row = piece * kPieceRows + j * 4 + group;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                if (piece < pieces && row < a.N && ok[i])
+                    q[j][i] = load16(x, uniform64(piece * kPieceRows * row_bytes), (j * 4 + group) * row_bytes + off[i]);
+                else
+                    q[j][i] = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    int64_t piece = member * kShortWaves + wave;
+    u32x4 raw[R][VPL];
+    fetch(piece, raw);
+    for (; piece < pieces; piece += stride) {
+        u32x4 nxt[R][VPL];
+        fetch(piece + stride, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int64_t row = piece * kPieceRows + j * 4 + group;
+            float s = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                float v[E];
+                io::unpack(raw[j][i], v);
+#pragma unroll
+                for (int e = 0; e < E; ++e) s += v[e] * v[e];
+            }
+            const float rs = 1.0f / sqrtf(row16_sum(s) * a.inv_D + a.eps);
+            if (row < a.N) {
+                if (gl == 0) rstd[row] = rs;
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) {
+                    if (ok[i]) {
+                        float v[E], o[E];
+                        io::unpack(raw[j][i], v);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) o[e] = (v[e] * rs) * W[i][e];
+                        store16(y, uniform64(piece * kPieceRows * row_bytes), (j * 4 + group) * row_bytes + off[i], io::pack(o));
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) raw[j][i] = nxt[j][i];
+        }
+    }
+}
+
+// One partial-sum slot per wave: slot (t*nb + member)*kShortWaves + wave of a.ws.
+template <typename Tag, int VPL, int R>
+__global__ __launch_bounds__(kShortWaves* kWave)
+void qknorm_short_bwd_kernel(const QkBwdArgs a) {
+    using io = IO<Tag>;
+    constexpr int E = io::E;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int group = lane >> 4, gl = lane & 15;
+    const uint32_t row_bytes = static_cast<uint32_t>(a.D) * io::kBytes;
+    const int t = blockIdx.x >= static_cast<unsigned>(a.nb) ? 1 : 0;
+    const int64_t member = static_cast<int64_t>(blockIdx.x) - static_cast<int64_t>(t) * a.nb;
+    const char* dy = static_cast<const char*>(t ? a.dy[1] : a.dy[0]);
+    const char* x = static_cast<const char*>(t ? a.x[1] : a.x[0]);
+    const void* wgt = t ? a.w[1] : a.w[0];
+    const float* rstd = t ? a.rstd[1] : a.rstd[0];
+    char* dx = static_cast<char*>(t ? a.dx[1] : a.dx[0]);
+
+    bool ok[VPL];
+    uint32_t off[VPL];
+    float W[VPL][E], acc[VPL][E];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int chunk = i * 16 + gl;
+        ok[i] = chunk < a.nchunks;
+        off[i] = static_cast<uint32_t>(chunk) * 16u;
+        u32x4 rw = u32x4{0u, 0u, 0u, 0u};
+        if (ok[i]) rw = load16_cached(wgt, 0, off[i]);
+        io::unpack(rw, W[i]);
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[i][e] = 0.0f;
+    }
+
+    constexpr int64_t kPieceRows = 4 * R;
+    const int64_t pieces = (a.N + kPieceRows - 1) / kPieceRows;
+    const int64_t stride = static_cast<int64_t>(a.nb) * kShortWaves;
+    auto fetch = [&](int64_t piece, u32x4 (&q)[2][R][VPL], float (&qrs)[R]) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int64_t row = piece * kPieceRows + j * 4 + group;
+            const bool live = piece < pieces && row < a.N;
+            qrs[j] = live ? rstd[row] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                if (live && ok[i]) {
+                    const int64_t base = uniform64(piece * kPieceRows * row_bytes);
+                    const uint32_t lo = (j * 4 + group) * row_bytes + off[i];
+                    q[0][j][i] = load16(dy, base, lo);
+                    q[1][j][i] = load16(x, base, lo);
+                } else {
+                    q[0][j][i] = u32x4{0u, 0u, 0u, 0u};
+                    q[1][j][i] = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        }
+    };
+    int64_t piece = member * kShortWaves + wave;
+    u32x4 raw[2][R][VPL];
+    float rs[R];
+    fetch(piece, raw, rs);
+    for (; piece < pieces; piece += stride) {
+        u32x4 nxt[2][R][VPL];
+        float nrs[R];
+        fetch(piece + stride, nxt, nrs);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int64_t row = piece * kPieceRows + j * 4 + group;
+            float dyv[VPL][E], hv[VPL][E];
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                float xv[E];
+                io::unpack(raw[0][j][i], dyv[i]);
+                io::unpack(raw[1][j][i], xv);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    hv[i][e] = xv[e] * rs[j];
+                    p += (dyv[i][e] * W[i][e]) * hv[i][e];
+                    acc[i][e] += dyv[i][e] * hv[i][e];
+                }
+            }
+            const float k2 = rs[j] * (row16_sum(p) * a.inv_D);
+            if (row < a.N) {
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) {
+                    if (ok[i]) {
+                        float o[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) o[e] = (dyv[i][e] * W[i][e]) * rs[j] - hv[i][e] * k2;
+                        store16(dx, uniform64(piece * kPieceRows * row_bytes), (j * 4 + group) * row_bytes + off[i], io::pack(o));
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            rs[j] = nrs[j];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                for (int i = 0; i < VPL; ++i) raw[s][j][i] = nxt[s][j][i];
+            }
+        }
+    }
+
+    // add the four groups of the wave (lanes l, l+16, l+32, l+48 hold the same features), then
+    // the first group writes the wave's slot
+    float* slot = a.ws + ((static_cast<int64_t>(t) * a.nb + member) * kShortWaves + wave) * a.D;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float v = acc[i][e];
+            v += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(((lane ^ 16) << 2), __builtin_bit_cast(int, v)));
+            v += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(((lane ^ 32) << 2), __builtin_bit_cast(int, v)));
+            acc[i][e] = v;
+        }
+        if (ok[i] && group == 0) {
+            f32x4* ps = reinterpret_cast<f32x4*>(slot + (i * 16 + gl) * E);
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q)
+                ps[q] = f32x4{acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]};
+        }
+    }
+}
+
 // Second pass: dw[t][d] = sum of the nb slots of tensor t, slots in ascending order split over 16
 // waves, the 16 wave sums then added in wave order.  grid.x = 2 * dblocks.
 struct QkReduceArgs {

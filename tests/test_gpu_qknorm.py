@@ -66,6 +66,13 @@ def test_qknorm_row_counts(N):
     run_qk(synth.make_qknorm_inputs(N, 1024, "bf16", 3200 + N), label="N=%d" % N)
 
 
+@pytest.mark.parametrize("N", [1, 3, 4, 5, 31, 32, 33, 127, 4099])
+@pytest.mark.parametrize("D,dtype", [(128, "bf16"), (256, "bf16"), (64, "bf16"), (64, "f32"), (72, "bf16")])
+def test_qknorm_short_rows(N, D, dtype):
+    # rows of at most 32 chunks take the 16-lanes-per-row kernels: ragged piece and group tails
+    run_qk(synth.make_qknorm_inputs(N, D, dtype, 3300 + N + D), label="short N=%d D=%d %s" % (N, D, dtype))
+
+
 def test_qknorm_per_head_view():
     # one head's width as the normalised dimension: [tokens*heads, 128]
     run_qk(synth.make_qknorm_inputs(300 * 40, 128, "bf16", 3004), label="per head")
