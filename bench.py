@@ -84,8 +84,19 @@ def cpu_baseline(D, sample_tokens, repeats=3):
             oracle.set_num_threads(cores)
         one = {"value": round((fwd_b + bwd_b) / t1 / 1e9, 3), "unit": "GB/s", "cores": 1,
                "tokens_per_s": round(sample_tokens / t1), "seconds": round(t1, 3)}
+    # the forward-only workload [1] (bf16 B=1 S=32760 D=1536), all cores, median of 3
+    inp1 = synth.make_inputs(1)
+    t1s = []
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        oracle.forward(inp1.x, inp1.shift, inp1.scale, 1e-6, B=1, S=inp1.T)
+        t1s.append(time.perf_counter() - t0)
+    d1 = sorted(t1s)[len(t1s) // 2]
+    cfg1 = {"workload": "configs[1] forward, 32760 x 1536", "value": round(inp1.T * (4 * inp1.D + 8) / d1 / 1e9, 3),
+            "unit": "GB/s", "cores": cores, "tokens_per_s": round(inp1.T / d1), "seconds": round(d1, 4)}
     return {"value": round((fwd_b + bwd_b) / dt / 1e9, 3), "unit": "GB/s", "cores": cores,
             "kind": "oracle", "tokens_per_s": round(sample_tokens / dt), "seconds": round(dt, 3),
+            "config1_forward": cfg1,
             "sample": "%d of the workload's 75600 tokens (fwd+bwd, float64 C, OpenMP over rows), "
                       "median of %d runs" % (sample_tokens, repeats),
             "one_thread": one}
