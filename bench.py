@@ -246,22 +246,25 @@ def _randn_bf16(torch, g, shape, dev, std=1.0, mean=0.0):
     return (torch.randn(*shape, generator=g, device=dev) * std + mean).to(torch.bfloat16)
 
 
-def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=None, rotate=1, seed=1):
-    """Forward and backward of one workload shape (bf16), timed with events on the launch stream.
+def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=None, rotate=1, seed=1, fp32=False):
+    """Forward and backward of one workload shape (bf16, or fp32 I/O), timed with events on the launch stream.
     `rotate` > 1 cycles through that many independent buffer sets so that a workload smaller
     than the 256 MB Infinity Cache still streams from HBM."""
     g = torch.Generator(device=dev)
     g.manual_seed(seed)
+    io_dt = torch.float32 if fp32 else torch.bfloat16
+    code = lnmod.LNMOD_F32 if fp32 else lnmod.LNMOD_BF16
+    elem = 4 if fp32 else 2
     T = int(sum(lengths)) if lengths is not None else B * S
     nseg = len(lengths) if lengths is not None else B
     per_token = mod == lnmod.LNMOD_PER_TOKEN
     mrows = T if per_token else nseg
     sets = []
     for _ in range(rotate):
-        x = _randn_bf16(torch, g, (T, D), dev)
-        dy = _randn_bf16(torch, g, (T, D), dev)
-        sh = _randn_bf16(torch, g, (mrows, D), dev, 0.1)
-        sc = _randn_bf16(torch, g, (mrows, D), dev, 0.1)
+        x = _randn_bf16(torch, g, (T, D), dev).to(io_dt)
+        dy = _randn_bf16(torch, g, (T, D), dev).to(io_dt)
+        sh = _randn_bf16(torch, g, (mrows, D), dev, 0.1).to(io_dt)
+        sc = _randn_bf16(torch, g, (mrows, D), dev, 0.1).to(io_dt)
         y, dx = torch.empty_like(x), torch.empty_like(x)
         if per_token:
             dsh, dsc = torch.empty_like(x), torch.empty_like(x)
@@ -285,28 +288,28 @@ def _run_workload(lnmod, torch, stream, st, dev, name, B, S, D, mod, lengths=Non
     def fwd():
         x, dy, sh, sc, y, dx, dsh, dsc = pick()
         if cu is not None:
-            rc = lnmod.lnmod_forward_varlen(x, sh, sc, cu, nseg, T, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16)
+            rc = lnmod.lnmod_forward_varlen(x, sh, sc, cu, nseg, T, D, 1e-6, st, y, mean, rstd, code)
         else:
-            rc = lnmod.lnmod_forward(x, sh, sc, B, S, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16, mod)
+            rc = lnmod.lnmod_forward(x, sh, sc, B, S, D, 1e-6, st, y, mean, rstd, code, mod)
         assert rc == 0, lnmod.lnmod_status_string(rc)
 
     def bwd():
         x, dy, sh, sc, y, dx, dsh, dsc = pick()
         if cu is not None:
             rc = lnmod.lnmod_backward_varlen(dy, x, None, sc, cu, nseg, T, D, 1e-6, st, mean, rstd, dx, dsh,
-                                             dsc, ws, ws.numel(), lnmod.LNMOD_BF16)
+                                             dsc, ws, ws.numel(), code)
         else:
             rc = lnmod.lnmod_backward(dy, x, None, sc, B, S, D, 1e-6, st, mean, rstd, dx, dsh, dsc, ws,
-                                      ws.numel(), lnmod.LNMOD_BF16, mod)
+                                      ws.numel(), code, mod)
         assert rc == 0, lnmod.lnmod_status_string(rc)
 
     fwd()
     torch.cuda.synchronize()
     f_ms = _time_ms(torch, stream, fwd)
     b_ms = _time_ms(torch, stream, bwd)
-    mod_bytes = 2 * D * 2                       # shift + scale, or scale + two per-token outputs
-    fwd_b = T * (4 * D + 8) + (T * mod_bytes if per_token else 0)
-    bwd_b = T * (6 * D + 8) + (T * 3 * D * 2 if per_token else 0)
+    mod_bytes = 2 * D * elem                    # shift + scale, or scale + two per-token outputs
+    fwd_b = T * (2 * elem * D + 8) + (T * mod_bytes if per_token else 0)
+    bwd_b = T * (3 * elem * D + 8) + (T * 3 * D * elem if per_token else 0)
     return {"workload": name, "tokens": T, "D": D,
             "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
@@ -412,6 +415,8 @@ def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused
                       seed=1004),
         _run_workload(lnmod, torch, stream, st, dev, "configs[4] varlen 24 segments T=%d D=5120" % sum(lengths),
                       24, 0, 5120, PS, lengths=lengths, seed=1005),
+        _run_workload(lnmod, torch, stream, st, dev, "fp32 I/O B=1 S=37800 D=5120 (the bytes of configs[2])",
+                      1, 37800, 5120, PS, seed=1006, fp32=True),
     ]
     res["gated"] = _run_gated(lnmod, torch, stream, st, dev, T, D)
     res["qknorm"] = _run_qknorm(lnmod, torch, stream, st, dev, T, D)
