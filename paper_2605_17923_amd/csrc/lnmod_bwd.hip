@@ -62,6 +62,10 @@ void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t
         else go_seg<Tag, 1, 5, TOK>(a, R, blocks, st);
         return;
     }
+    if (sp.VPL == 3) {                       // choose_split_bwd: 4 waves, 3 chunks per lane
+        go_seg<Tag, 3, 4, TOK>(a, R, blocks, st);
+        return;
+    }
     switch (sp.K) {
         case 2: go_seg<Tag, VPL_WIDE, 2, TOK>(a, R, blocks, st); break;
         case 3: go_seg<Tag, VPL_WIDE, 3, TOK>(a, R, blocks, st); break;
