@@ -13,7 +13,14 @@ namespace {
 // features per lane on half the waves (819 against 870 us on 75600 x 5120 bf16).
 constexpr int kWaveCounts[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
 
+// Exception: bf16 rows of 9 to 16 times 512 features take 8 waves with two chunks per lane (two
+// waves on every SIMD of the CU) rather than 10 to 16 waves with one (D = 5120: 798 against
+// 819 us; at D = 8192 sixteen waves would also halve the registers a wave may use).
 Split gated_split(int nchunks, int dtype) {
+    if (dtype == 0) {
+        const int cols = (nchunks + kWave - 1) / kWave;
+        if (cols >= 9 && cols <= 16) return {8, 2};
+    }
     const int vpl = dtype == 0 ? 1 : 2;
     const int need = (nchunks + kWave * vpl - 1) / (kWave * vpl);
     for (int k : kWaveCounts)
@@ -52,6 +59,10 @@ void go(const GatedBwdArgs& a, int R, int64_t blocks, hipStream_t st) {
 
 template <typename Tag, int VPL>
 void dispatch(const GatedBwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t st) {
+    if (sp.VPL != VPL) {                     // the 8-wave, two-chunk split of wide bf16 rows
+        go<Tag, 2, 8>(a, R, blocks, st);
+        return;
+    }
     switch (sp.K) {
         case 1: go<Tag, VPL, 1>(a, R, blocks, st); break;
         case 2: go<Tag, VPL, 2>(a, R, blocks, st); break;

@@ -46,7 +46,7 @@ struct GatedFwdArgs {
 
 constexpr int gated_fwd_waves_per_eu(int vpl, int elems, int rows, bool ln) {
     // per lane and chunk: gate (and 1+scale, shift) in fp32, two packed copies of x and u per row
-    const int regs = vpl * ((ln ? 3 : 1) * elems + 16 * rows) + 32;
+    const int regs = vpl * ((ln ? 3 : 1) * elems + 16 * rows) + 64;
     const int w = 512 / regs;
     return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }

@@ -124,7 +124,8 @@ def test_gated_many_samples():
 
 
 def test_gated_zero_gate_matches_plain_forward():
-    # gate = 0: h must equal x bit for bit and y, mean, rstd must equal lnmod_forward's
+    # gate = 0: h must equal x bit for bit; y, mean, rstd must agree with lnmod_forward's up to the
+    # order of the fp32 row sums (the two kernels may split a row over different numbers of waves)
     inp = synth.make_inputs(2, S=515)
     x = to_device(inp.x, "bf16").view(1, 515, 5120)
     u = to_device(synth.make_gated_extras(inp, 5).u, "bf16").view(1, 515, 5120)
@@ -132,8 +133,12 @@ def test_gated_zero_gate_matches_plain_forward():
     h, y, mean, rstd = lnmod.gated_forward(x, u, torch.zeros_like(shift), shift, scale)
     y2, mean2, rstd2 = lnmod.forward(x, shift, scale)
     torch.cuda.synchronize()
-    assert torch.equal(h, x) and torch.equal(y, y2)
-    assert torch.equal(mean, mean2.reshape(-1)) and torch.equal(rstd, rstd2.reshape(-1))
+    assert torch.equal(h, x)
+    yd, y2d = y.double(), y2.double()
+    assert float(((yd - y2d).abs() / (y2d.abs() + 1e-3)).max()) <= 2.0 ** -7       # at most one bf16 rounding apart
+    assert float((yd != y2d).double().mean()) < 0.02
+    assert torch.allclose(mean, mean2.reshape(-1), rtol=1e-6, atol=1e-6)
+    assert torch.allclose(rstd, rstd2.reshape(-1), rtol=1e-6, atol=0)
 
 
 def test_gated_results_repeat_bit_for_bit():
