@@ -87,14 +87,15 @@ struct BwdGo {
 
 // Short rows (at most 32 chunks, e.g. one head's width): 16 lanes per row, four rows per wave.
 constexpr int kShortMaxChunks = 32;
-constexpr int kShortBlocksPerCu = 2;                 // blocks of 4 waves, over both tensors
+constexpr int kShortFwdBlocksPerCu = 8;              // blocks of 4 waves, over both tensors
+constexpr int kShortBwdBlocksPerCu = 2;
 
 // rows per wave and step = 4 * R: about 8 KB of loads per wave and step
 template <int VPL> constexpr int short_fwd_r() { return VPL == 1 ? 8 : 4; }
 template <int VPL> constexpr int short_bwd_r() { return VPL == 1 ? 4 : 2; }
 
-int32_t short_blocks_per_tensor(int64_t N, int rows_per_piece) {
-    int64_t nb = static_cast<int64_t>(kNumCU) * kShortBlocksPerCu / 2;
+int32_t short_blocks_per_tensor(int64_t N, int rows_per_piece, int per_cu) {
+    int64_t nb = static_cast<int64_t>(kNumCU) * per_cu / 2;
     const int64_t pieces = (N + rows_per_piece - 1) / rows_per_piece;
     const int64_t need = (pieces + kShortWaves - 1) / kShortWaves;
     if (nb > need) nb = need;
@@ -108,7 +109,7 @@ int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype) {
     const int nchunks = static_cast<int>(D / E);
     if (nchunks <= kShortMaxChunks) {                // one slot per wave
         const int r = nchunks <= 16 ? short_bwd_r<1>() : short_bwd_r<2>();
-        return short_blocks_per_tensor(N, 4 * r) * kShortWaves;
+        return short_blocks_per_tensor(N, 4 * r, kShortBwdBlocksPerCu) * kShortWaves;
     }
     const Split sp = choose_split(nchunks, dtype);
     return blocks_per_tensor(N, bwd_blocks_per_cu(sp.K));
@@ -130,7 +131,7 @@ hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void
     a.inv_D = 1.0f / static_cast<float>(D);
     if (a.nchunks <= kShortMaxChunks) {
         const bool one = a.nchunks <= 16;
-        a.nb = short_blocks_per_tensor(N, 4 * (one ? short_fwd_r<1>() : short_fwd_r<2>()));
+        a.nb = short_blocks_per_tensor(N, 4 * (one ? short_fwd_r<1>() : short_fwd_r<2>()), kShortFwdBlocksPerCu);
         const dim3 grid(static_cast<unsigned>(2 * a.nb)), block(kShortWaves * kWave);
         if (dtype == 0) {
             if (one) hipLaunchKernelGGL((qknorm_short_fwd_kernel<bf16_io, 1, short_fwd_r<1>()>), grid, block, 0, st, a);
