@@ -59,7 +59,8 @@ void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t
     }
     if (sp.VPL == 1) {                       // only choose_split_bwd produces these
         if (sp.K == 3) go_seg<Tag, 1, 3, TOK>(a, R, blocks, st);
-        else go_seg<Tag, 1, 5, TOK>(a, R, blocks, st);
+        else if (sp.K == 5) go_seg<Tag, 1, 5, TOK>(a, R, blocks, st);
+        else go_seg<Tag, 1, 6, TOK>(a, R, blocks, st);
         return;
     }
     if (sp.VPL == 3) {                       // choose_split_bwd: 4 waves, 3 chunks per lane

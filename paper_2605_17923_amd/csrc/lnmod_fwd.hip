@@ -13,6 +13,7 @@ constexpr int kTokRows = 1;        // rows per block and step, modulation stream
 // the next step in flight, stream best.
 int fwd_blocks_per_cu(int K) {
     if (K == 1) return 4;
+    if (K == 3) return 2;              // three waves alone leave a CU short (D = 3072: 5.3 against 4.5 TB/s)
     const int b = 5 / K;
     return b < 1 ? 1 : b;
 }

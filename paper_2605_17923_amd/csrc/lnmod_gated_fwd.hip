@@ -12,6 +12,7 @@ constexpr int kRows = 2;           // rows per block and step
 // forward (one input, one output) carry twice the bytes here, so the same counts are kept.
 int blocks_per_cu(int K) {
     if (K == 1) return 4;
+    if (K == 3) return 2;              // three waves alone leave a CU short
     const int b = 5 / K;
     return b < 1 ? 1 : b;
 }

@@ -89,6 +89,8 @@ inline Split choose_split(int nchunks, int dtype) {
 // Rows of 3 or 5 times 512 features (D = 1536, 2560) are shared by 3 or 5 waves with one chunk
 // per lane instead of being taken by one wave or padded: every block writes a partial-sum slot,
 // and a third as many blocks (of three waves) means a third as many slots to write and add up.
+// Rows of 6 times 512 features (D = 3072) likewise go to 6 waves with one chunk per lane (one
+// block per CU) rather than 3 waves with two (6.3 against 5.8 TB/s).
 // Rows of 9 to 12 times 512 features (D = 4608 .. 6144) go to 4 waves with 3 chunks per lane
 // rather than 5 or 6 waves with 2: one wave per SIMD keeps the four SIMDs of a CU evenly loaded,
 // where five waves put two on one of them (D = 5120: 372 against 380 us).
@@ -97,6 +99,7 @@ inline Split choose_split_bwd(int nchunks, int dtype) {
         const int k = nchunks / 64;
         if (k == 3 || k == 5) return {k, 1};
     }
+    if (dtype == 0 && nchunks > 5 * 64 && nchunks <= 6 * 64) return {6, 1};
     if (dtype == 0) {
         const int need = (nchunks + 63) / 64;
         if (need >= 9 && need <= 12) return {4, 3};

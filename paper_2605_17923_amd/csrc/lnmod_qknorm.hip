@@ -11,6 +11,7 @@ constexpr int kRows = 2;           // rows per block and step
 // Resident blocks per CU over both tensors together; each tensor gets half of them.
 int fwd_blocks_per_cu(int K) {
     if (K == 1) return 4;
+    if (K == 3) return 2;              // three waves alone leave a CU short
     const int b = 5 / K;
     return b < 1 ? 1 : b;
 }

@@ -164,8 +164,9 @@ def test_multi_sample_ranges_cross_blocks(B, S):
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 8), ("bf16", 520), ("bf16", 1024), ("bf16", 1544),
-                                     ("bf16", 3072), ("bf16", 4096), ("bf16", 6144), ("bf16", 7000),
-                                     ("bf16", 8192),
+                                     ("bf16", 1152), ("bf16", 2048), ("bf16", 2432), ("bf16", 2560), ("bf16", 2816),
+                                     ("bf16", 3072), ("bf16", 4096), ("bf16", 4608), ("bf16", 4616), ("bf16", 5632),
+                                     ("bf16", 6144), ("bf16", 7000), ("bf16", 8192),
                                      ("f32", 8), ("f32", 100), ("f32", 260), ("f32", 1024),
                                      ("f32", 3076), ("f32", 5120), ("f32", 8192)])
 def test_hidden_sizes(dtype, D):
