@@ -6,27 +6,13 @@
 namespace lnmod {
 namespace {
 
-// With the software pipeline about 5 or 6 waves per CU, each with 20 to 40 KB of loads in
-// flight, reach the highest HBM bandwidth; more concurrent waves lower it.
-int blocks_per_cu(int K) {
-    if (K == 1) return 4;
-    const int b = 6 / K;
-    return b < 1 ? 1 : b;
-}
-
-// Per-token modulation streams three inputs and three outputs per row, one row per step: twice
-// the waves.
+// Per-token modulation streams three inputs and three outputs per row, one row per step for
+// rows of 4 KB and more: twice the waves of the per-sample kernels of the rule-based split.
 int tok_blocks_per_cu(int K) {
     if (K == 1) return 8;
     const int b = 10 / K;
     return b < 1 ? 1 : b;
 }
-
-// Rows per block and step.  Two rows (about 8 KB of loads per wave and step, as much again
-// in flight for the next step) are robust; one row per step is faster on some runs and 35 %
-// slower on others, depending on the clocks the GPU happens to run at.  With per-token
-// modulation a third input streams along, and one row per step carries about the same bytes.
-int rows_per_step(int K, int64_t row_bytes) { (void)K; (void)row_bytes; return 2; }
 int rows_per_step_tok(int K, int64_t row_bytes) { return (K > 1 && row_bytes >= 4096) ? 1 : 2; }
 
 template <typename Tag, int VPL, int K, int R, bool TOK>
@@ -44,37 +30,51 @@ void go_seg(const BwdArgs& a, int R, int64_t blocks, hipStream_t st) {
     else go_seg_r<Tag, VPL, K, 2, TOK>(a, blocks, st);
 }
 
-// VPL_WIDE: chunks per lane when several waves share a row (fixed by the dtype)
-template <typename Tag, int VPL_WIDE, bool TOK>
-void dispatch_seg(const BwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t st) {
-    if (sp.K == 1) {
-        switch (sp.VPL) {
-            case 1: go_seg<Tag, 1, 1, TOK>(a, R, blocks, st); break;
-            case 2: go_seg<Tag, 2, 1, TOK>(a, R, blocks, st); break;
-            case 3: go_seg<Tag, 3, 1, TOK>(a, R, blocks, st); break;
-            case 4: go_seg<Tag, 4, 1, TOK>(a, R, blocks, st); break;
-            default: go_seg<Tag, 6, 1, TOK>(a, R, blocks, st); break;
+// Every (VPL, K) the shape table, the fp32 rule and the per-token rule can ask for.
+template <typename Tag, bool TOK>
+bool dispatch_seg(const BwdArgs& a, int VPL, int K, int R, int64_t blocks, hipStream_t st) {
+    switch (VPL * 100 + K) {
+        case 101: go_seg<Tag, 1, 1, TOK>(a, R, blocks, st); return true;
+        case 201: go_seg<Tag, 2, 1, TOK>(a, R, blocks, st); return true;
+        case 301: go_seg<Tag, 3, 1, TOK>(a, R, blocks, st); return true;
+        default: break;
+    }
+    if constexpr (IO<Tag>::E == 8) {                     // bf16 rule: two chunks per lane when shared
+        switch (VPL * 100 + K) {
+            case 202: go_seg<Tag, 2, 2, TOK>(a, R, blocks, st); return true;
+            case 203: go_seg<Tag, 2, 3, TOK>(a, R, blocks, st); return true;
+            case 204: go_seg<Tag, 2, 4, TOK>(a, R, blocks, st); return true;
+            case 205: go_seg<Tag, 2, 5, TOK>(a, R, blocks, st); return true;
+            case 206: go_seg<Tag, 2, 6, TOK>(a, R, blocks, st); return true;
+            case 208: go_seg<Tag, 2, 8, TOK>(a, R, blocks, st); return true;
+            default: break;
         }
-        return;
     }
-    if (sp.VPL == 1) {                       // only choose_split_bwd produces these
-        if (sp.K == 3) go_seg<Tag, 1, 3, TOK>(a, R, blocks, st);
-        else if (sp.K == 5) go_seg<Tag, 1, 5, TOK>(a, R, blocks, st);
-        else go_seg<Tag, 1, 6, TOK>(a, R, blocks, st);
-        return;
+    if constexpr (IO<Tag>::E == 8 && !TOK) {             // bf16 shape table only
+        switch (VPL * 100 + K) {
+            case 103: go_seg<Tag, 1, 3, TOK>(a, R, blocks, st); return true;
+            case 104: go_seg<Tag, 1, 4, TOK>(a, R, blocks, st); return true;
+            case 105: go_seg<Tag, 1, 5, TOK>(a, R, blocks, st); return true;
+            case 106: go_seg<Tag, 1, 6, TOK>(a, R, blocks, st); return true;
+            case 304: go_seg<Tag, 3, 4, TOK>(a, R, blocks, st); return true;
+            case 306: go_seg<Tag, 3, 6, TOK>(a, R, blocks, st); return true;
+            default: break;
+        }
     }
-    if (sp.VPL == 3) {                       // choose_split_bwd: 4 waves, 3 chunks per lane
-        go_seg<Tag, 3, 4, TOK>(a, R, blocks, st);
-        return;
+    if constexpr (IO<Tag>::E == 4) {                     // fp32 rule: up to 6 chunks alone, else 4 per lane
+        switch (VPL * 100 + K) {
+            case 401: go_seg<Tag, 4, 1, TOK>(a, R, blocks, st); return true;
+            case 601: go_seg<Tag, 6, 1, TOK>(a, R, blocks, st); return true;
+            case 402: go_seg<Tag, 4, 2, TOK>(a, R, blocks, st); return true;
+            case 403: go_seg<Tag, 4, 3, TOK>(a, R, blocks, st); return true;
+            case 404: go_seg<Tag, 4, 4, TOK>(a, R, blocks, st); return true;
+            case 405: go_seg<Tag, 4, 5, TOK>(a, R, blocks, st); return true;
+            case 406: go_seg<Tag, 4, 6, TOK>(a, R, blocks, st); return true;
+            case 408: go_seg<Tag, 4, 8, TOK>(a, R, blocks, st); return true;
+            default: break;
+        }
     }
-    switch (sp.K) {
-        case 2: go_seg<Tag, VPL_WIDE, 2, TOK>(a, R, blocks, st); break;
-        case 3: go_seg<Tag, VPL_WIDE, 3, TOK>(a, R, blocks, st); break;
-        case 4: go_seg<Tag, VPL_WIDE, 4, TOK>(a, R, blocks, st); break;
-        case 5: go_seg<Tag, VPL_WIDE, 5, TOK>(a, R, blocks, st); break;
-        case 6: go_seg<Tag, VPL_WIDE, 6, TOK>(a, R, blocks, st); break;
-        default: go_seg<Tag, VPL_WIDE, 8, TOK>(a, R, blocks, st); break;
-    }
+    return false;                                        // no such instantiation
 }
 
 BwdArgs make_args(const Problem& p, const void* dy, const void* x, const void* scale,
@@ -110,9 +110,8 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float* p, int64_t n) {
 
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Split sp = choose_split_bwd(static_cast<int>(D / E), dtype);
-    const int R = rows_per_step(sp.K, D * (dtype == 0 ? 2 : 4));
-    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K), R, 90);
+    const Shape sh = bwd_shape(static_cast<int>(D / E), dtype);
+    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
 }
 
 hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const void* scale,
@@ -120,13 +119,13 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
                           float* dscale, float* ws, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
-    const Split sp = choose_split_bwd(a.nchunks, p.dtype);
+    const Shape sh = bwd_shape(a.nchunks, p.dtype);
     const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    const int R = rows_per_step(sp.K, p.D * (p.dtype == 0 ? 2 : 4));
-    if (p.dtype == 0) dispatch_seg<bf16_io, 2, false>(a, sp, R, pl.blocks, st);
-    else dispatch_seg<f32_io, 4, false>(a, sp, R, pl.blocks, st);
+    const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
+                                 : dispatch_seg<f32_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
+    if (!ok) return hipErrorInvalidConfiguration;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -155,9 +154,9 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
     const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * tok_blocks_per_cu(sp.K), R, 90);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    if (p.dtype == 0) dispatch_seg<bf16_io, 2, true>(a, sp, R, pl.blocks, st);
-    else dispatch_seg<f32_io, 4, true>(a, sp, R, pl.blocks, st);
-    return hipGetLastError();
+    const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, true>(a, sp.VPL, sp.K, R, pl.blocks, st)
+                                 : dispatch_seg<f32_io, true>(a, sp.VPL, sp.K, R, pl.blocks, st);
+    return ok ? hipGetLastError() : hipErrorInvalidConfiguration;
 }
 
 hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t st) {

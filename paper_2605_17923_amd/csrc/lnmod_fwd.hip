@@ -6,19 +6,10 @@
 namespace lnmod {
 namespace {
 
-constexpr int kFwdRows = 2;        // rows per block and step, one modulation row per segment
 constexpr int kTokRows = 1;        // rows per block and step, modulation streamed per token
 
-// About 4 or 5 waves per CU, each with its chunks of the current step in registers and those of
-// the next step in flight, stream best.
-int fwd_blocks_per_cu(int K) {
-    if (K == 1) return 4;
-    if (K == 3) return 2;              // three waves alone leave a CU short (D = 3072: 5.3 against 4.5 TB/s)
-    const int b = 5 / K;
-    return b < 1 ? 1 : b;
-}
-
-// Per-token modulation streams three inputs per row and takes one row per step: twice the waves.
+// Per-token modulation streams three inputs per row and takes one row per step: about ten
+// waves per CU.
 int tok_blocks_per_cu(int K) {
     if (K == 1) return 8;
     const int b = 10 / K;
@@ -45,15 +36,8 @@ FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void
     return a;
 }
 
-// fp32 rows shared by several waves carry twice the bytes per wave of bf16 rows: one row per
-// step and twice the blocks stream better there (266 against 287 us on 37800 x 5120).
-constexpr bool wide_fp32(int elems_per_chunk, int K) { return elems_per_chunk == 4 && K > 1; }
-
-int seg_rows(int dtype, int K) { return wide_fp32(dtype == 0 ? 8 : 4, K) ? 1 : kFwdRows; }
-
-template <typename Tag, int VPL, int K, int MODE>
-void go_split(const FwdArgs& a, int64_t blocks, hipStream_t st) {
-    constexpr int R = MODE == kModToken ? kTokRows : wide_fp32(IO<Tag>::E, K) ? 1 : kFwdRows;
+template <typename Tag, int VPL, int K, int R, int MODE>
+void go_r(const FwdArgs& a, int64_t blocks, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
     if (a.nchunks == K * VPL * kWave)
         hipLaunchKernelGGL((fwd_split_kernel<Tag, VPL, K, R, true, MODE>), grid, block, 0, st, a);
@@ -61,27 +45,61 @@ void go_split(const FwdArgs& a, int64_t blocks, hipStream_t st) {
         hipLaunchKernelGGL((fwd_split_kernel<Tag, VPL, K, R, false, MODE>), grid, block, 0, st, a);
 }
 
-// VPL_WIDE: chunks per lane when several waves share a row (fixed by the dtype)
-template <typename Tag, int VPL_WIDE, int MODE>
-void dispatch_split(const FwdArgs& a, Split sp, int64_t blocks, hipStream_t st) {
-    if (sp.K == 1) {
-        switch (sp.VPL) {
-            case 1: go_split<Tag, 1, 1, MODE>(a, blocks, st); break;
-            case 2: go_split<Tag, 2, 1, MODE>(a, blocks, st); break;
-            case 3: go_split<Tag, 3, 1, MODE>(a, blocks, st); break;
-            case 4: go_split<Tag, 4, 1, MODE>(a, blocks, st); break;
-            default: go_split<Tag, 6, 1, MODE>(a, blocks, st); break;
+template <typename Tag, int VPL, int K, int MODE>
+void go(const FwdArgs& a, int R, int64_t blocks, hipStream_t st) {
+    if constexpr (MODE == kModToken) {
+        go_r<Tag, VPL, K, kTokRows, MODE>(a, blocks, st);
+    } else {
+        if (R == 1) go_r<Tag, VPL, K, 1, MODE>(a, blocks, st);
+        else go_r<Tag, VPL, K, 2, MODE>(a, blocks, st);
+    }
+}
+
+// Every (VPL, K) the shape table, the fp32 rule and the per-token rule can ask for.
+template <typename Tag, int MODE>
+bool dispatch(const FwdArgs& a, int VPL, int K, int R, int64_t blocks, hipStream_t st) {
+    switch (VPL * 100 + K) {
+        case 101: go<Tag, 1, 1, MODE>(a, R, blocks, st); return true;
+        case 201: go<Tag, 2, 1, MODE>(a, R, blocks, st); return true;
+        case 301: go<Tag, 3, 1, MODE>(a, R, blocks, st); return true;
+        default: break;
+    }
+    if constexpr (IO<Tag>::E == 8) {                     // bf16
+        switch (VPL * 100 + K) {
+            case 202: go<Tag, 2, 2, MODE>(a, R, blocks, st); return true;
+            case 204: go<Tag, 2, 4, MODE>(a, R, blocks, st); return true;
+            case 205: go<Tag, 2, 5, MODE>(a, R, blocks, st); return true;
+            default: break;
         }
-        return;
+        if constexpr (MODE == kModToken) {               // rule-based split of the per-token kernels
+            switch (VPL * 100 + K) {
+                case 203: go<Tag, 2, 3, MODE>(a, R, blocks, st); return true;
+                case 206: go<Tag, 2, 6, MODE>(a, R, blocks, st); return true;
+                case 208: go<Tag, 2, 8, MODE>(a, R, blocks, st); return true;
+                default: break;
+            }
+        } else {                                         // shape table
+            switch (VPL * 100 + K) {
+                case 302: go<Tag, 3, 2, MODE>(a, R, blocks, st); return true;
+                case 304: go<Tag, 3, 4, MODE>(a, R, blocks, st); return true;
+                case 306: go<Tag, 3, 6, MODE>(a, R, blocks, st); return true;
+                default: break;
+            }
+        }
+    } else {                                             // fp32 rule: up to 6 chunks alone, else 4 per lane
+        switch (VPL * 100 + K) {
+            case 401: go<Tag, 4, 1, MODE>(a, R, blocks, st); return true;
+            case 601: go<Tag, 6, 1, MODE>(a, R, blocks, st); return true;
+            case 402: go<Tag, 4, 2, MODE>(a, R, blocks, st); return true;
+            case 403: go<Tag, 4, 3, MODE>(a, R, blocks, st); return true;
+            case 404: go<Tag, 4, 4, MODE>(a, R, blocks, st); return true;
+            case 405: go<Tag, 4, 5, MODE>(a, R, blocks, st); return true;
+            case 406: go<Tag, 4, 6, MODE>(a, R, blocks, st); return true;
+            case 408: go<Tag, 4, 8, MODE>(a, R, blocks, st); return true;
+            default: break;
+        }
     }
-    switch (sp.K) {
-        case 2: go_split<Tag, VPL_WIDE, 2, MODE>(a, blocks, st); break;
-        case 3: go_split<Tag, VPL_WIDE, 3, MODE>(a, blocks, st); break;
-        case 4: go_split<Tag, VPL_WIDE, 4, MODE>(a, blocks, st); break;
-        case 5: go_split<Tag, VPL_WIDE, 5, MODE>(a, blocks, st); break;
-        case 6: go_split<Tag, VPL_WIDE, 6, MODE>(a, blocks, st); break;
-        default: go_split<Tag, VPL_WIDE, 8, MODE>(a, blocks, st); break;
-    }
+    return false;                                        // no such instantiation
 }
 
 template <int MODE>
@@ -89,17 +107,20 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    const Split sp = choose_split(a.nchunks, p.dtype);
+    Shape sh;
+    if (MODE == kModToken) {
+        const Split sp = choose_split(a.nchunks, p.dtype);
+        sh = Shape{sp.K, sp.VPL, kTokRows, tok_blocks_per_cu(sp.K)};
+    } else {
+        sh = fwd_shape(a.nchunks, p.dtype);
+    }
     const bool per_segment = MODE == kModSegment || MODE == kModOnly;
-    const int rows = MODE == kModToken ? kTokRows : seg_rows(p.dtype, sp.K);
-    const int per_cu = MODE == kModToken ? tok_blocks_per_cu(sp.K)
-                                         : fwd_blocks_per_cu(sp.K) * (kFwdRows / rows);
-    const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * per_cu, rows, 20);
+    const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 20);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    if (p.dtype == 0) dispatch_split<bf16_io, 2, MODE>(a, sp, pl.blocks, st);
-    else dispatch_split<f32_io, 4, MODE>(a, sp, pl.blocks, st);
-    return hipGetLastError();
+    const bool ok = p.dtype == 0 ? dispatch<bf16_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
+                                 : dispatch<f32_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
+    return ok ? hipGetLastError() : hipErrorInvalidConfiguration;
 }
 
 }  // namespace

@@ -85,26 +85,74 @@ inline Split choose_split(int nchunks, int dtype) {
     return {k, per_feat16};
 }
 
-// The backward's split.  As the forward's, with two exceptions for bf16 rows.
-// Rows of 3 or 5 times 512 features (D = 1536, 2560) are shared by 3 or 5 waves with one chunk
-// per lane instead of being taken by one wave or padded: every block writes a partial-sum slot,
-// and a third as many blocks (of three waves) means a third as many slots to write and add up.
-// Rows of 6 times 512 features (D = 3072) likewise go to 6 waves with one chunk per lane (one
-// block per CU) rather than 3 waves with two (6.3 against 5.8 TB/s).
-// Rows of 9 to 12 times 512 features (D = 4608 .. 6144) go to 4 waves with 3 chunks per lane
-// rather than 5 or 6 waves with 2: one wave per SIMD keeps the four SIMDs of a CU evenly loaded,
-// where five waves put two on one of them (D = 5120: 372 against 380 us).
-inline Split choose_split_bwd(int nchunks, int dtype) {
-    if (dtype == 0 && nchunks % 128 == 64) {
-        const int k = nchunks / 64;
-        if (k == 3 || k == 5) return {k, 1};
-    }
-    if (dtype == 0 && nchunks > 5 * 64 && nchunks <= 6 * 64) return {6, 1};
+// Launch shape of the per-sample / per-segment kernels: K waves per row, VPL chunks per lane, R
+// rows per block and step, per_cu resident blocks per CU.  For bf16 the shape comes from a table
+// indexed by the row length in units of 64 chunks (512 features).  The table was measured, not
+// derived: every (K, VPL, R, per_cu) with at most 25 % padding and 3 to 16 waves per CU was timed
+// on one sample of about 770 MB per tensor at D = 1152 ... 8192, three times on different
+// machines, and the entry is the shape with the best worst run.  What the winners share: a wave
+// count that is a multiple of the four SIMDs of a CU (or a single block of 5 or 6 waves), and
+// 16 to 32 KB of row data in flight per CU.  fp32 keeps the rule-based split.
+struct Shape {
+    int K;
+    int VPL;
+    int R;
+    int per_cu;
+};
+
+inline Shape fwd_shape(int nchunks, int dtype) {
     if (dtype == 0) {
-        const int need = (nchunks + 63) / 64;
-        if (need >= 9 && need <= 12) return {4, 3};
+        const int cols = (nchunks + 63) / 64;
+        switch (cols) {
+            case 1: return {1, 1, 2, 4};
+            case 2: return {1, 2, 2, 4};
+            // D = 1536: three blocks per CU are 3 % faster on 126 000 rows, four are 4 % faster on the
+            // 32 760 rows of the Wan-1.3B workload
+            case 3: return nchunks == 192 ? Shape{1, 3, 2, 4} : Shape{1, 3, 1, 8};
+            case 4: return {2, 2, 1, 4};
+            case 5:
+            case 6: return {2, 3, 1, 4};
+            case 7:
+            case 8: return {4, 2, 2, 1};
+            case 9:
+            case 10: return {5, 2, 2, 1};
+            case 11:
+            case 12: return {4, 3, 1, 2};
+            default: return {6, 3, 1, 1};
+        }
     }
-    return choose_split(nchunks, dtype);
+    const Split sp = choose_split(nchunks, dtype);
+    // fp32 rows shared by several waves carry twice the bytes per wave of bf16 rows: one row per
+    // step and twice the blocks stream better there (266 against 287 us on 37800 x 5120)
+    const int R = sp.K > 1 ? 1 : 2;
+    int per_cu = sp.K == 1 ? 4 : sp.K == 3 ? 2 : 5 / sp.K;
+    if (per_cu < 1) per_cu = 1;
+    return {sp.K, sp.VPL, R, per_cu * (2 / R)};
+}
+
+inline Shape bwd_shape(int nchunks, int dtype) {
+    if (dtype == 0) {
+        const int cols = (nchunks + 63) / 64;
+        switch (cols) {
+            case 1: return {1, 1, 2, 4};
+            case 2: return {1, 2, 2, 4};
+            case 3: return {3, 1, 1, nchunks == 192 ? 3 : 4};
+            case 4: return {4, 1, 2, 2};
+            case 5: return {5, 1, 2, 1};
+            case 6: return {6, 1, 2, 1};
+            case 7:
+            case 8: return {4, 2, 2, 1};
+            case 9:
+            case 10:
+            case 11:
+            case 12: return {4, 3, 2, 1};
+            default: return {6, 3, 2, 1};
+        }
+    }
+    const Split sp = choose_split(nchunks, dtype);
+    int per_cu = sp.K == 1 ? 4 : 6 / sp.K;
+    if (per_cu < 1) per_cu = 1;
+    return {sp.K, sp.VPL, 2, per_cu};
 }
 
 // The backward's plan for this problem: the same function sizes the workspace, drives the main

@@ -335,3 +335,47 @@ def test_calls_can_be_captured_in_a_hip_graph():
         torch.cuda.synchronize()
         for got, ref in zip((y, mean, rstd, dx, dsh, dsc), want):
             assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
+
+
+def test_every_supported_hidden_size_launches():
+    # every D the header promises (multiples of 8 for bf16, of 4 for fp32, up to 8192) must map
+    # to an instantiated kernel in all four entry points; the results of 3 rows are checked against
+    # a float64 torch expression of the definition (not the oracle: 3000 sizes, tiny rows)
+    st = torch.cuda.current_stream().cuda_stream
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    B, S = 1, 3
+    for dtype, code, step, tol in ((torch.bfloat16, lnmod.LNMOD_BF16, 8, 3e-2), (torch.float32, lnmod.LNMOD_F32, 4, 2e-4)):
+        bad = []
+        for D in range(8, 8193, step):
+            x = torch.randn(S, D, generator=g, device="cuda").to(dtype)
+            dy = torch.randn(S, D, generator=g, device="cuda").to(dtype)
+            sh = (0.1 * torch.randn(1, D, generator=g, device="cuda")).to(dtype)
+            sc = (0.1 * torch.randn(1, D, generator=g, device="cuda")).to(dtype)
+            y, dx = torch.empty_like(x), torch.empty_like(x)
+            mean, rstd = torch.empty(S, device="cuda"), torch.empty(S, device="cuda")
+            dsh, dsc = torch.empty(1, D, device="cuda"), torch.empty(1, D, device="cuda")
+            ws = lnmod.workspace(B, S, D, "cuda")
+            for mod in (lnmod.LNMOD_PER_SAMPLE, lnmod.LNMOD_PER_TOKEN):
+                tok = mod == lnmod.LNMOD_PER_TOKEN
+                shm = sh.expand(S, D).contiguous() if tok else sh
+                scm = sc.expand(S, D).contiguous() if tok else sc
+                o1 = torch.empty(S, D, device="cuda", dtype=dtype) if tok else dsh
+                o2 = torch.empty(S, D, device="cuda", dtype=dtype) if tok else dsc
+                rc1 = lnmod.lnmod_forward(x, shm, scm, B, S, D, 1e-6, st, y, mean, rstd, code, mod)
+                rc2 = lnmod.lnmod_backward(dy, x, None, scm, B, S, D, 1e-6, st, mean, rstd, dx, o1, o2, ws, ws.numel(),
+                                           code, mod)
+                if rc1 != 0 or rc2 != 0:
+                    bad.append((D, mod, rc1, rc2))
+                    continue
+                if D % 136 == 0 or D in (8, 8192):        # spot-check the numbers
+                    xd, dyd, scd, shd = x.double(), dy.double(), sc.double(), sh.double()
+                    mu = xd.mean(1, keepdim=True)
+                    r = 1.0 / torch.sqrt(((xd - mu) ** 2).mean(1, keepdim=True) + 1e-6)
+                    xh = (xd - mu) * r
+                    gg = dyd * (1 + scd)
+                    want_dx = r * (gg - gg.mean(1, keepdim=True) - xh * (gg * xh).mean(1, keepdim=True))
+                    assert float((y.double() - (xh * (1 + scd) + shd)).abs().max()) <= tol * 4, (D, mod)
+                    assert float((dx.double() - want_dx).abs().max()) <= tol * float(want_dx.abs().max() + 1), (D, mod)
+        torch.cuda.synchronize()
+        assert not bad, "launch failed for %d sizes, first %r" % (len(bad), bad[:5])
