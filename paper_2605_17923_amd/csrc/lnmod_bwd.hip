@@ -6,15 +6,6 @@
 namespace lnmod {
 namespace {
 
-// Per-token modulation streams three inputs and three outputs per row, one row per step for
-// rows of 4 KB and more: twice the waves of the per-sample kernels of the rule-based split.
-int tok_blocks_per_cu(int K) {
-    if (K == 1) return 8;
-    const int b = 10 / K;
-    return b < 1 ? 1 : b;
-}
-int rows_per_step_tok(int K, int64_t row_bytes) { return (K > 1 && row_bytes >= 4096) ? 1 : 2; }
-
 template <typename Tag, int VPL, int K, int R, bool TOK>
 void go_seg_r(const BwdArgs& a, int64_t blocks, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
@@ -149,13 +140,12 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
                           void* dscale, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, dshift, dscale, nullptr, E);
-    const Split sp = choose_split(a.nchunks, p.dtype);
-    const int R = rows_per_step_tok(sp.K, p.D * (p.dtype == 0 ? 2 : 4));
-    const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * tok_blocks_per_cu(sp.K), R, 90);
+    const Shape sh = tok_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
+    const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, true>(a, sp.VPL, sp.K, R, pl.blocks, st)
-                                 : dispatch_seg<f32_io, true>(a, sp.VPL, sp.K, R, pl.blocks, st);
+    const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, true>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
+                                 : dispatch_seg<f32_io, true>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
     return ok ? hipGetLastError() : hipErrorInvalidConfiguration;
 }
 

@@ -6,16 +6,6 @@
 namespace lnmod {
 namespace {
 
-constexpr int kTokRows = 1;        // rows per block and step, modulation streamed per token
-
-// Per-token modulation streams three inputs per row and takes one row per step: about ten
-// waves per CU.
-int tok_blocks_per_cu(int K) {
-    if (K == 1) return 8;
-    const int b = 10 / K;
-    return b < 1 ? 1 : b;
-}
-
 FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
                   float* mean, float* rstd, int E) {
     FwdArgs a;
@@ -47,12 +37,8 @@ void go_r(const FwdArgs& a, int64_t blocks, hipStream_t st) {
 
 template <typename Tag, int VPL, int K, int MODE>
 void go(const FwdArgs& a, int R, int64_t blocks, hipStream_t st) {
-    if constexpr (MODE == kModToken) {
-        go_r<Tag, VPL, K, kTokRows, MODE>(a, blocks, st);
-    } else {
-        if (R == 1) go_r<Tag, VPL, K, 1, MODE>(a, blocks, st);
-        else go_r<Tag, VPL, K, 2, MODE>(a, blocks, st);
-    }
+    if (R == 1) go_r<Tag, VPL, K, 1, MODE>(a, blocks, st);
+    else go_r<Tag, VPL, K, 2, MODE>(a, blocks, st);
 }
 
 // Every (VPL, K) the shape table, the fp32 rule and the per-token rule can ask for.
@@ -107,13 +93,7 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    Shape sh;
-    if (MODE == kModToken) {
-        const Split sp = choose_split(a.nchunks, p.dtype);
-        sh = Shape{sp.K, sp.VPL, kTokRows, tok_blocks_per_cu(sp.K)};
-    } else {
-        sh = fwd_shape(a.nchunks, p.dtype);
-    }
+    const Shape sh = MODE == kModToken ? tok_fwd_shape(a.nchunks, p.dtype) : fwd_shape(a.nchunks, p.dtype);
     const bool per_segment = MODE == kModSegment || MODE == kModOnly;
     const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 20);
     a.rows_per_cluster = pl.rows_per_cluster;

@@ -7,35 +7,36 @@
 namespace lnmod {
 namespace {
 
-// A lane holds 8 features of a row (one bf16 chunk, two fp32 chunks): with five fp32 values per
-// feature living in registers (1+scale, gate, three running sums) and four packed input streams
-// prefetched one step ahead, that is what fits without spilling, and it streams better than 16
-// features per lane on half the waves (819 against 870 us on 75600 x 5120 bf16).
+// Launch shape (see Shape in lnmod_launch.hpp).  A lane holds 8 features of a row (one bf16 chunk,
+// two fp32 chunks): with five fp32 values per feature living in registers (1+scale, gate, three
+// running sums) and four packed input streams prefetched one step ahead, that is what fits
+// without spilling.  bf16 rows of 9 to 16 times 512 features take two chunks per lane on 6 or 8
+// waves instead (whole multiples of the four SIMDs; D = 5120: 798 against 819 us, and sixteen
+// waves would halve the registers a wave may use).  One block per CU once a row needs three
+// waves; two rows per step for rows up to 8 KB.  Timed like the other tables (D = 1536 ... 8192).
 constexpr int kWaveCounts[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
 
-// Exception: bf16 rows of 9 to 16 times 512 features take 8 waves with two chunks per lane (two
-// waves on every SIMD of the CU) rather than 10 to 16 waves with one (D = 5120: 798 against
-// 819 us; at D = 8192 sixteen waves would also halve the registers a wave may use).
-Split gated_split(int nchunks, int dtype) {
-    if (dtype == 0) {
-        const int cols = (nchunks + kWave - 1) / kWave;
-        if (cols >= 9 && cols <= 16) return {8, 2};
-    }
+Shape gated_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
     const int vpl = dtype == 0 ? 1 : 2;
     const int need = (nchunks + kWave * vpl - 1) / (kWave * vpl);
+    int K = 16;
     for (int k : kWaveCounts)
-        if (k >= need) return {k, vpl};
-    return {16, vpl};                        // not reached: D <= 8192 needs at most 16 waves
+        if (k >= need) {
+            K = k;
+            break;
+        }
+    int per_cu = 6 / K;
+    if (per_cu < 1 || K >= 3) per_cu = 1;
+    Shape sh{K, vpl, row_bytes <= 8192 ? 2 : 1, per_cu};
+    if (dtype == 0) {
+        const int cols = (nchunks + kWave - 1) / kWave;
+        if (cols == 4) sh.R = 1;                         // D = 2048: 5.97 against 5.6 TB/s
+        if (cols >= 9 && cols <= 10) sh = {8, 2, 1, 1};
+        if (cols >= 11 && cols <= 12) sh = {6, 2, 1, 1};
+        if (cols >= 13) sh = {8, 2, 1, 1};
+    }
+    return sh;
 }
-
-int blocks_per_cu(int K) {
-    const int b = 6 / K;
-    return b < 1 ? 1 : b;
-}
-
-// Four input streams per row: one row per step already gives a wave as many bytes in flight as
-// two rows give the plain backward; short rows take two.
-int rows_per_step(int64_t row_bytes) { return row_bytes < 4096 ? 2 : 1; }
 
 template <typename Tag, int VPL, int K, int R>
 void go_r(const GatedBwdArgs& a, int64_t blocks, hipStream_t st) {
@@ -48,7 +49,8 @@ void go_r(const GatedBwdArgs& a, int64_t blocks, hipStream_t st) {
 
 template <typename Tag, int VPL, int K>
 void go(const GatedBwdArgs& a, int R, int64_t blocks, hipStream_t st) {
-    if constexpr (K <= 4) {                  // rows shorter than 4 KB never need more waves
+    // two rows per step only for rows up to 8 KB: at most 8 waves of 8 features per lane
+    if constexpr (K <= 8 && (VPL == 1 || IO<Tag>::E == 4)) {
         if (R == 2) {
             go_r<Tag, VPL, K, 2>(a, blocks, st);
             return;
@@ -58,22 +60,26 @@ void go(const GatedBwdArgs& a, int R, int64_t blocks, hipStream_t st) {
 }
 
 template <typename Tag, int VPL>
-void dispatch(const GatedBwdArgs& a, Split sp, int R, int64_t blocks, hipStream_t st) {
-    if (sp.VPL != VPL) {                     // the 8-wave, two-chunk split of wide bf16 rows
-        go<Tag, 2, 8>(a, R, blocks, st);
-        return;
+bool dispatch(const GatedBwdArgs& a, Shape sh, int64_t blocks, hipStream_t st) {
+    if (sh.VPL != VPL) {                     // the two-chunk shapes of wide bf16 rows
+        if (sh.VPL != 2) return false;
+        if (sh.K == 8) go<Tag, 2, 8>(a, sh.R, blocks, st);
+        else if (sh.K == 6) go<Tag, 2, 6>(a, sh.R, blocks, st);
+        else return false;
+        return true;
     }
-    switch (sp.K) {
-        case 1: go<Tag, VPL, 1>(a, R, blocks, st); break;
-        case 2: go<Tag, VPL, 2>(a, R, blocks, st); break;
-        case 3: go<Tag, VPL, 3>(a, R, blocks, st); break;
-        case 4: go<Tag, VPL, 4>(a, R, blocks, st); break;
-        case 5: go<Tag, VPL, 5>(a, R, blocks, st); break;
-        case 6: go<Tag, VPL, 6>(a, R, blocks, st); break;
-        case 8: go<Tag, VPL, 8>(a, R, blocks, st); break;
-        case 10: go<Tag, VPL, 10>(a, R, blocks, st); break;
-        case 12: go<Tag, VPL, 12>(a, R, blocks, st); break;
-        default: go<Tag, VPL, 16>(a, R, blocks, st); break;
+    switch (sh.K) {
+        case 1: go<Tag, VPL, 1>(a, sh.R, blocks, st); return true;
+        case 2: go<Tag, VPL, 2>(a, sh.R, blocks, st); return true;
+        case 3: go<Tag, VPL, 3>(a, sh.R, blocks, st); return true;
+        case 4: go<Tag, VPL, 4>(a, sh.R, blocks, st); return true;
+        case 5: go<Tag, VPL, 5>(a, sh.R, blocks, st); return true;
+        case 6: go<Tag, VPL, 6>(a, sh.R, blocks, st); return true;
+        case 8: go<Tag, VPL, 8>(a, sh.R, blocks, st); return true;
+        case 10: go<Tag, VPL, 10>(a, sh.R, blocks, st); return true;
+        case 12: go<Tag, VPL, 12>(a, sh.R, blocks, st); return true;
+        case 16: go<Tag, VPL, 16>(a, sh.R, blocks, st); return true;
+        default: return false;
     }
 }
 
@@ -81,9 +87,8 @@ void dispatch(const GatedBwdArgs& a, Split sp, int R, int64_t blocks, hipStream_
 
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Split sp = gated_split(static_cast<int>(D / E), dtype);
-    const int R = rows_per_step(D * (dtype == 0 ? 2 : 4));
-    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K), R, 90);
+    const Shape sh = gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4));
+    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
 }
 
 hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, const void* h,
@@ -108,13 +113,13 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Split sp = gated_split(a.nchunks, p.dtype);
+    const Shape sh = gated_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
     const RowPlan pl = gated_bwd_plan(p.T, p.nseg, p.D, p.dtype);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    const int R = rows_per_step(p.D * (p.dtype == 0 ? 2 : 4));
-    if (p.dtype == 0) dispatch<bf16_io, 1>(a, sp, R, pl.blocks, st);
-    else dispatch<f32_io, 2>(a, sp, R, pl.blocks, st);
+    const bool ok = p.dtype == 0 ? dispatch<bf16_io, 1>(a, sh, pl.blocks, st)
+                                 : dispatch<f32_io, 2>(a, sh, pl.blocks, st);
+    if (!ok) return hipErrorInvalidConfiguration;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 

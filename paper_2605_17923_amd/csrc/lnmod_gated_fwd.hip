@@ -6,10 +6,10 @@
 namespace lnmod {
 namespace {
 
-constexpr int kRows = 2;           // rows per block and step
-
-// Two input and two output streams per row: the waves per CU that stream best for the plain
-// forward (one input, one output) carry twice the bytes here, so the same counts are kept.
+// Launch shape (see Shape in lnmod_launch.hpp).  The rule: the split of choose_split, two rows per
+// step, about five waves per CU.  For bf16 the widths that were timed (every shape with at most
+// 25 % padding, D = 1536 ... 8192, two machines) override it; the winners again are multiples of
+// the four SIMDs of a CU or one block of five waves.
 int blocks_per_cu(int K) {
     if (K == 1) return 4;
     if (K == 3) return 2;              // three waves alone leave a CU short
@@ -17,24 +17,29 @@ int blocks_per_cu(int K) {
     return b < 1 ? 1 : b;
 }
 
-// bf16 rows of 9 to 12 times 512 features (D = 4608 .. 6144) go to 4 waves with 3 chunks per
-// lane and one row per step: one wave per SIMD keeps the four SIMDs of a CU evenly loaded, where
-// five waves put two on one of them (D = 5120: 537 against 560 us).
-constexpr bool balanced4(int VPL, int K) { return VPL == 3 && K == 4; }
-
-Split gated_fwd_split(int nchunks, int dtype) {
-    if (dtype == 0) {
-        const int need = (nchunks + kWave - 1) / kWave;
-        if (need >= 9 && need <= 12) return {4, 3};
+Shape gated_fwd_shape(int nchunks, int dtype, bool ln) {
+    const Split sp = choose_split(nchunks, dtype);
+    Shape sh{sp.K, sp.VPL, 2, blocks_per_cu(sp.K)};
+    if (dtype == 0 && ln) {
+        switch ((nchunks + kWave - 1) / kWave) {
+            case 3: sh = {1, 3, 1, 4}; break;
+            case 4: sh = {2, 2, 1, 3}; break;
+            case 5:
+            case 6: sh = {3, 2, 1, 2}; break;
+            case 7:
+            case 8: sh = {5, 2, 2, 1}; break;       // D = 4096: five waves, the fifth idle, beat four
+            case 9:
+            case 10:
+            case 11:
+            case 12: sh = {4, 3, 1, 1}; break;      // D = 5120: 537 against 560 us for five waves x 2
+            default: break;
+        }
     }
-    return choose_split(nchunks, dtype);
+    return sh;
 }
 
-int rows_per_step(Split sp) { return balanced4(sp.VPL, sp.K) ? 1 : kRows; }
-
-template <typename Tag, int VPL, int K, bool LN>
-void go(const GatedFwdArgs& a, int64_t blocks, hipStream_t st) {
-    constexpr int R = balanced4(VPL, K) ? 1 : kRows;
+template <typename Tag, int VPL, int K, int R, bool LN>
+void go_r(const GatedFwdArgs& a, int64_t blocks, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
     if (a.nchunks == K * VPL * kWave)
         hipLaunchKernelGGL((gated_fwd_kernel<Tag, VPL, K, R, true, LN>), grid, block, 0, st, a);
@@ -42,34 +47,50 @@ void go(const GatedFwdArgs& a, int64_t blocks, hipStream_t st) {
         hipLaunchKernelGGL((gated_fwd_kernel<Tag, VPL, K, R, false, LN>), grid, block, 0, st, a);
 }
 
-template <typename Tag, int VPL_WIDE, bool LN>
-void dispatch(const GatedFwdArgs& a, Split sp, int64_t blocks, hipStream_t st) {
-    if (sp.K == 1) {
-        switch (sp.VPL) {
-            case 1: go<Tag, 1, 1, LN>(a, blocks, st); break;
-            case 2: go<Tag, 2, 1, LN>(a, blocks, st); break;
-            case 3: go<Tag, 3, 1, LN>(a, blocks, st); break;
-            default:                             // 4 and 6 chunks per lane: fp32 rows only
-                if constexpr (IO<Tag>::E == 4) {
-                    if (sp.VPL == 4) go<Tag, 4, 1, LN>(a, blocks, st);
-                    else go<Tag, 6, 1, LN>(a, blocks, st);
-                }
-                break;
+template <typename Tag, int VPL, int K, bool LN>
+void go(const GatedFwdArgs& a, int R, int64_t blocks, hipStream_t st) {
+    if constexpr (LN && IO<Tag>::E == 8) {               // only the bf16 table asks for one row
+        if (R == 1) {
+            go_r<Tag, VPL, K, 1, LN>(a, blocks, st);
+            return;
         }
-        return;
     }
-    if (balanced4(sp.VPL, sp.K)) {
-        go<Tag, 3, 4, LN>(a, blocks, st);
-        return;
+    go_r<Tag, VPL, K, 2, LN>(a, blocks, st);
+}
+
+template <typename Tag, bool LN>
+bool dispatch(const GatedFwdArgs& a, Shape sh, int64_t blocks, hipStream_t st) {
+    switch (sh.VPL * 100 + sh.K) {
+        case 101: go<Tag, 1, 1, LN>(a, sh.R, blocks, st); return true;
+        case 201: go<Tag, 2, 1, LN>(a, sh.R, blocks, st); return true;
+        case 301: go<Tag, 3, 1, LN>(a, sh.R, blocks, st); return true;
+        default: break;
     }
-    switch (sp.K) {
-        case 2: go<Tag, VPL_WIDE, 2, LN>(a, blocks, st); break;
-        case 3: go<Tag, VPL_WIDE, 3, LN>(a, blocks, st); break;
-        case 4: go<Tag, VPL_WIDE, 4, LN>(a, blocks, st); break;
-        case 5: go<Tag, VPL_WIDE, 5, LN>(a, blocks, st); break;
-        case 6: go<Tag, VPL_WIDE, 6, LN>(a, blocks, st); break;
-        default: go<Tag, VPL_WIDE, 8, LN>(a, blocks, st); break;
+    if constexpr (IO<Tag>::E == 8) {
+        switch (sh.VPL * 100 + sh.K) {
+            case 202: go<Tag, 2, 2, LN>(a, sh.R, blocks, st); return true;
+            case 203: go<Tag, 2, 3, LN>(a, sh.R, blocks, st); return true;
+            case 204: go<Tag, 2, 4, LN>(a, sh.R, blocks, st); return true;
+            case 205: go<Tag, 2, 5, LN>(a, sh.R, blocks, st); return true;
+            case 206: go<Tag, 2, 6, LN>(a, sh.R, blocks, st); return true;
+            case 208: go<Tag, 2, 8, LN>(a, sh.R, blocks, st); return true;
+            case 304: go<Tag, 3, 4, LN>(a, sh.R, blocks, st); return true;
+            default: break;
+        }
+    } else {
+        switch (sh.VPL * 100 + sh.K) {
+            case 401: go<Tag, 4, 1, LN>(a, sh.R, blocks, st); return true;
+            case 601: go<Tag, 6, 1, LN>(a, sh.R, blocks, st); return true;
+            case 402: go<Tag, 4, 2, LN>(a, sh.R, blocks, st); return true;
+            case 403: go<Tag, 4, 3, LN>(a, sh.R, blocks, st); return true;
+            case 404: go<Tag, 4, 4, LN>(a, sh.R, blocks, st); return true;
+            case 405: go<Tag, 4, 5, LN>(a, sh.R, blocks, st); return true;
+            case 406: go<Tag, 4, 6, LN>(a, sh.R, blocks, st); return true;
+            case 408: go<Tag, 4, 8, LN>(a, sh.R, blocks, st); return true;
+            default: break;
+        }
     }
+    return false;
 }
 
 template <bool LN>
@@ -92,14 +113,13 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Split sp = LN ? gated_fwd_split(a.nchunks, p.dtype) : choose_split(a.nchunks, p.dtype);
-    const RowPlan pl = plan_rows(p.T, p.nseg, static_cast<int64_t>(kNumCU) * blocks_per_cu(sp.K),
-                                 rows_per_step(sp), 20);
+    const Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
+    const RowPlan pl = plan_rows(p.T, p.nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 20);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    if (p.dtype == 0) dispatch<bf16_io, 2, LN>(a, sp, pl.blocks, st);
-    else dispatch<f32_io, 4, LN>(a, sp, pl.blocks, st);
-    return hipGetLastError();
+    const bool ok = p.dtype == 0 ? dispatch<bf16_io, LN>(a, sh, pl.blocks, st)
+                                 : dispatch<f32_io, LN>(a, sh, pl.blocks, st);
+    return ok ? hipGetLastError() : hipErrorInvalidConfiguration;
 }
 
 }  // namespace

@@ -155,6 +155,50 @@ inline Shape bwd_shape(int nchunks, int dtype) {
     return {sp.K, sp.VPL, 2, per_cu};
 }
 
+// Per-token modulation (three input streams forward; three in, three out backward).  The rule:
+// the split of choose_split, one row per step for shared rows of 4 KB and more (backward) or
+// always (forward), about ten waves per CU.  For bf16 the widths that were timed (same procedure
+// as above, D = 1536 ... 8192) override it.
+inline Shape tok_fwd_shape(int nchunks, int dtype) {
+    const Split sp = choose_split(nchunks, dtype);
+    int per_cu = sp.K == 1 ? 8 : 10 / sp.K;
+    if (per_cu < 1) per_cu = 1;
+    Shape sh{sp.K, sp.VPL, 1, per_cu};
+    if (dtype == 0) {
+        switch ((nchunks + 63) / 64) {
+            case 3: sh = {1, 3, 2, 4}; break;
+            case 4: sh = {2, 2, 1, 4}; break;
+            case 5:
+            case 6: sh = {3, 2, 1, 2}; break;
+            case 7:
+            case 8: sh = {4, 2, 2, 2}; break;
+            case 11:
+            case 12: sh = {6, 2, 2, 2}; break;
+            default: break;
+        }
+    }
+    return sh;
+}
+
+inline Shape tok_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
+    const Split sp = choose_split(nchunks, dtype);
+    int per_cu = sp.K == 1 ? 8 : 10 / sp.K;
+    if (per_cu < 1) per_cu = 1;
+    Shape sh{sp.K, sp.VPL, (sp.K > 1 && row_bytes >= 4096) ? 1 : 2, per_cu};
+    if (dtype == 0) {
+        switch ((nchunks + 63) / 64) {
+            case 3: sh = {1, 3, 1, 3}; break;
+            case 4: sh = {2, 2, 1, 2}; break;
+            case 5:
+            case 6: sh = {3, 2, 1, 2}; break;
+            case 7:
+            case 8: sh = {4, 2, 1, 1}; break;
+            default: break;
+        }
+    }
+    return sh;
+}
+
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
 // kernel's grid and tells the second pass which partial-sum slots belong to a segment.
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
