@@ -253,7 +253,8 @@ int lnmod_gated_backward(const void* dy, const void* dh, const void* h, const vo
         !dshift || !dscale)
         return LNMOD_EINVAL;
     if (!aligned16(dy) || !aligned16(dh) || !aligned16(h) || !aligned16(u) || !aligned16(gate) ||
-        !aligned16(scale) || !aligned16(dx) || !aligned16(du))
+        !aligned16(scale) || !aligned16(dx) || !aligned16(du) || !aligned16(dgate) ||
+        !aligned16(dshift) || !aligned16(dscale))
         return LNMOD_EALIGN;
     if (!workspace || workspace_size < gated_workspace_bytes(B_or_nseg, T, D)) return LNMOD_EWORKSPACE;
     if (!aligned16(workspace)) return LNMOD_EALIGN;

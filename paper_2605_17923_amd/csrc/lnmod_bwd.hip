@@ -99,6 +99,17 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float* p, int64_t n) {
 
 }  // namespace
 
+hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
+    const ReduceShape sh = reduce_shape(r.seg.nseg, r.nsum, r.D, clusters, r.nb);
+    const int V = sh.V, W = sh.W;
+    r.dblocks = static_cast<int32_t>((r.D + kWave * V - 1) / (kWave * V));
+    const dim3 grid(static_cast<unsigned>(r.seg.nseg * r.nsum * r.dblocks)), block(W * kWave);
+    if (V == 4) hipLaunchKernelGGL(bwd_reduce_kernel<4>, grid, block, 0, st, r);
+    else if (V == 2) hipLaunchKernelGGL(bwd_reduce_kernel<2>, grid, block, 0, st, r);
+    else hipLaunchKernelGGL(bwd_reduce_kernel<1>, grid, block, 0, st, r);
+    return hipGetLastError();
+}
+
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
     const Shape sh = bwd_shape(static_cast<int>(D / E), dtype);
@@ -122,17 +133,16 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
 
     ReduceArgs r;
     r.ws = ws;
-    r.dshift = dshift;
-    r.dscale = dscale;
+    r.out[0] = dshift;
+    r.out[1] = dscale;
+    r.out[2] = nullptr;
     r.seg = a.seg;
     r.T = p.T;
     r.rows_per_cluster = a.rows_per_cluster;
     r.nb = a.nb;
     r.D = a.D;
-    r.dblocks = static_cast<int32_t>((p.D + kWave - 1) / kWave);
-    const dim3 grid(static_cast<unsigned>(p.nseg * 2 * r.dblocks));
-    hipLaunchKernelGGL(bwd_reduce_kernel<0>, grid, dim3(kReduceWaves * kWave), 0, st, r);
-    return hipGetLastError();
+    r.nsum = 2;
+    return launch_reduce(r, pl.clusters, st);
 }
 
 hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const void* scale,

@@ -123,7 +123,7 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    GatedReduceArgs r;
+    ReduceArgs r;
     r.ws = ws;
     r.out[0] = dshift;
     r.out[1] = dscale;
@@ -133,10 +133,8 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
     r.rows_per_cluster = a.rows_per_cluster;
     r.nb = a.nb;
     r.D = a.D;
-    r.dblocks = static_cast<int32_t>((p.D + kWave - 1) / kWave);
-    const dim3 grid(static_cast<unsigned>(p.nseg * 3 * r.dblocks));
-    hipLaunchKernelGGL(gated_reduce_kernel<0>, grid, dim3(kReduceWaves * kWave), 0, st, r);
-    return hipGetLastError();
+    r.nsum = 3;
+    return launch_reduce(r, pl.clusters, st);
 }
 
 }  // namespace lnmod

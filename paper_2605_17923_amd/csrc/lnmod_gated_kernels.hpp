@@ -509,48 +509,6 @@ void gated_bwd_kernel(const GatedBwdArgs a) {
     }
 }
 
-// Second pass: dshift / dscale / dgate [m, d] = sum of the partial slots of segment m, slots in
-// ascending order split over 16 waves, the 16 wave sums then added in wave order (bitwise
-// reproducible).  grid.x = nseg * 3 * dblocks, decoded as (segment, which sum, 64 features).
-struct GatedReduceArgs {
-    const float* ws;
-    float* out[3];           // dshift, dscale, dgate: [nseg, D] each
-    Segments seg;
-    int64_t T;
-    int64_t rows_per_cluster;
-    int32_t nb;
-    int32_t D;
-    int32_t dblocks;
-};
-
-template <int kUnused = 0>
-__global__ __launch_bounds__(kReduceWaves* kWave) void gated_reduce_kernel(const GatedReduceArgs a) {
-    __shared__ float red[kReduceWaves][kWave];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    const int64_t bid = blockIdx.x;
-    const int d = static_cast<int>(bid % a.dblocks) * kWave + lane;
-    const int which = static_cast<int>((bid / a.dblocks) % 3);
-    const int64_t m = bid / (3 * static_cast<int64_t>(a.dblocks));
-    int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
-    if (n0 < 0) n0 = 0;                       // a malformed table must not lead outside ws
-    if (n1 > a.T) n1 = a.T;
-    float acc = 0.0f;
-    if (n1 > n0 && d < a.D) {
-        const int64_t c_lo = n0 / a.rows_per_cluster, c_hi = (n1 - 1) / a.rows_per_cluster;
-        const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
-        for (int64_t sl = s_lo + wave; sl < s_hi; sl += kReduceWaves)
-            acc += a.ws[(sl * 3 + which) * a.D + d];
-    }
-    red[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0 && d < a.D) {
-        float t = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kReduceWaves; ++w) t += red[w][lane];
-        float* out = which == 0 ? a.out[0] : which == 1 ? a.out[1] : a.out[2];
-        out[m * a.D + d] = t;
-    }
-}
+// The second pass is bwd_reduce_kernel with three sums per slot.
 
 }  // namespace lnmod

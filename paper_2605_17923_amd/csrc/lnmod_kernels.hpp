@@ -718,53 +718,72 @@ void bwd_seg_kernel(const BwdArgs a) {
     }
 }
 
-// Second pass: dshift/dscale[m, d] = sum of the partial slots of segment m, slots in ascending
-// block order split over 16 waves (wave w takes slots w, w+16, ...), the 16 wave sums then added
-// in wave order.  The order depends only on the shapes, so results repeat bit for bit.
+// Second pass: out[k][m, d] = sum of the partial slots of segment m, k < nsum (dshift, dscale
+// and, for the gated operator, dgate).  A block takes 64 * V consecutive features of one sum of
+// one segment; its W = blockDim.x / 64 waves split the slots in ascending order (wave w takes
+// slots w, w + W, ...), and the W wave sums are then added in wave order.  V and W are chosen
+// from the shapes alone, so results repeat bit for bit.
 struct ReduceArgs {
-    const float* ws;
-    float* dshift;           // [nseg, D]
-    float* dscale;
+    const float* ws;         // [nslots][nsum][D]
+    float* out[3];           // [nseg, D] each
     Segments seg;
     int64_t T;
     int64_t rows_per_cluster;
     int32_t nb;              // blocks per cluster = partial slots per (cluster, segment)
     int32_t D;
-    int32_t dblocks;         // ceil(D / 64)
+    int32_t dblocks;         // ceil(D / (64 * V))
+    int32_t nsum;            // 2 or 3
 };
 
-constexpr int kReduceWaves = 16;
+constexpr int kReduceWaves = 16;     // most waves a reduce block may have
 
-// (a template only so that the header can be included in several translation units)
-// grid.x = nseg * 2 * dblocks, decoded as (segment, dshift|dscale, block of 64 features)
-template <int kUnused = 0>
+template <int V> struct FVec { typedef float type __attribute__((ext_vector_type(V))); };
+template <> struct FVec<1> { typedef float type; };
+
+// grid.x = nseg * nsum * dblocks, decoded as (segment, which sum, block of 64 * V features)
+template <int V>
 __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const ReduceArgs a) {
-    __shared__ float red[kReduceWaves][kWave];
+    using vec = typename FVec<V>::type;
+    __shared__ vec red[kReduceWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
+    const int W = blockDim.x >> 6;
     const int64_t bid = blockIdx.x;
-    const int d = static_cast<int>(bid % a.dblocks) * kWave + lane;
-    const int which = static_cast<int>((bid / a.dblocks) & 1);      // 0: dshift, 1: dscale
-    const int64_t m = bid / (2 * static_cast<int64_t>(a.dblocks));
+    const int d = (static_cast<int>(bid % a.dblocks) * kWave + lane) * V;
+    const int which = static_cast<int>((bid / a.dblocks) % a.nsum);
+    const int64_t m = bid / (static_cast<int64_t>(a.nsum) * a.dblocks);
     int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
     if (n0 < 0) n0 = 0;                       // a malformed table must not lead outside ws
     if (n1 > a.T) n1 = a.T;
-    float acc = 0.0f;
+    vec acc = vec(0.0f);
     if (n1 > n0 && d < a.D) {
         // clusters c_lo..c_hi touch this segment; (cluster c, segment m) owns slots (c+m)*nb ..
         const int64_t c_lo = n0 / a.rows_per_cluster, c_hi = (n1 - 1) / a.rows_per_cluster;
         const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
-        for (int64_t sl = s_lo + wave; sl < s_hi; sl += kReduceWaves)
-            acc += a.ws[(sl * 2 + which) * a.D + d];
-    }
-    red[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0 && d < a.D) {
-        float t = 0.0f;
+        const float* base = a.ws + static_cast<int64_t>(which) * a.D + d;
+        const int64_t pitch = static_cast<int64_t>(a.nsum) * a.D;
+        // four slots requested before the first is added; the additions keep slot order
+        for (int64_t sl = s_lo + wave; sl < s_hi; sl += 4 * W) {
+            vec v[4];
 #pragma unroll
-        for (int w = 0; w < kReduceWaves; ++w) t += red[w][lane];
-        (which == 0 ? a.dshift : a.dscale)[m * a.D + d] = t;
+            for (int u = 0; u < 4; ++u) {
+                const int64_t su = sl + static_cast<int64_t>(u) * W;
+                v[u] = su < s_hi ? *reinterpret_cast<const vec*>(base + su * pitch) : vec(0.0f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += v[u];
+        }
     }
+    if (W > 1) {
+        red[wave][lane] = acc;
+        __syncthreads();
+        if (wave == 0) {
+            acc = red[0][lane];
+            for (int w = 1; w < W; ++w) acc += red[w][lane];
+        }
+    }
+    if (wave == 0 && d < a.D)
+        *reinterpret_cast<vec*>(a.out[which] + m * a.D + d) = acc;
 }
 
 // =============================================================================================

@@ -232,6 +232,27 @@ inline Shape tok_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
 inline int64_t bwd_slots(const RowPlan& p, int64_t nseg) { return (p.clusters + nseg) * p.nb; }
 
+// Shape of the second pass: V features per lane, W waves per block.  Wide lanes need enough
+// (segment, sum, feature-block) triples to fill the chip; a wave should have about four slots
+// to add, and a block never more than 16 waves.
+struct ReduceShape {
+    int V;
+    int W;
+};
+
+inline ReduceShape reduce_shape(int64_t nseg, int nsum, int64_t D, int64_t clusters, int64_t nb) {
+    ReduceShape sh{1, 1};
+    const int64_t triples = nseg * nsum;
+    if (triples * ((D + 255) / 256) >= 256) sh.V = 4;
+    else if (triples * ((D + 127) / 128) >= 256) sh.V = 2;
+    const int64_t slots = nb * (1 + (clusters - 1) / nseg);   // typical slots of one segment
+    while (sh.W < 16 && sh.W * 2 * 4 <= slots) sh.W *= 2;
+    return sh;
+}
+
+struct ReduceArgs;
+hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st);
+
 hipError_t launch_fwd_seg(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* y, float* mean, float* rstd, hipStream_t st);
 hipError_t launch_fwd_tok(const Problem& p, const void* x, const void* shift, const void* scale,
