@@ -113,7 +113,11 @@ hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
     const Shape sh = bwd_shape(static_cast<int>(D / E), dtype);
-    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
+    // a row moves 3 D elements (dy, x, dx), a slot 2 D floats that are written and read back
+    const double elem = dtype == 0 ? 2.0 : 4.0;
+    const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 3.0 * elem / 5.8e6;
+    return plan_rows_slots(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, stream_us,
+                           16.0 / (3.0 * elem));
 }
 
 hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const void* scale,
@@ -151,7 +155,7 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, dshift, dscale, nullptr, E);
     const Shape sh = tok_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
-    const RowPlan pl = plan_rows(p.T, 1, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
+    const RowPlan pl = plan_rows(p.T, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, true>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)

@@ -99,8 +99,8 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
     const bool per_segment = MODE == kModSegment || MODE == kModOnly;
     // bytes of x and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
-    const RowPlan pl = plan_rows(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 20,
-                                 per_segment ? pick_clusters(stream_us, p.nseg) : 1);
+    const RowPlan pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
+                                          sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch<bf16_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)

@@ -88,7 +88,11 @@ bool dispatch(const GatedBwdArgs& a, Shape sh, int64_t blocks, hipStream_t st) {
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
     const Shape sh = gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4));
-    return plan_rows(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 90);
+    // a row moves 6 D elements (dy, dh, h, u, dx, du), a slot 3 D floats written and read back
+    const double elem = dtype == 0 ? 2.0 : 4.0;
+    const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 6.0 * elem / 5.8e6;
+    return plan_rows_slots(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, stream_us,
+                           24.0 / (6.0 * elem));
 }
 
 hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, const void* h,

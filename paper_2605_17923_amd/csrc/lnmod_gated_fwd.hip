@@ -116,8 +116,8 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
     const Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
     // bytes of x, u, h and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (p.dtype == 0 ? 8.0 : 16.0) / 6.0e6;
-    const RowPlan pl = plan_rows(p.T, p.nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, 20,
-                                 pick_clusters(stream_us, p.nseg));
+    const RowPlan pl = plan_rows_clusters(p.T, p.nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R,
+                                          pick_clusters(stream_us, p.nseg));
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch<bf16_io, LN>(a, sh, pl.blocks, st)

@@ -58,29 +58,17 @@ inline int64_t pick_clusters(double stream_us, int64_t nseg) {
     return best;
 }
 
-// max_blocks: resident blocks wanted; rows_per_step: rows one block takes per iteration;
-// overhead_div: nb * (nseg - 1) is kept below T / overhead_div - blocks; min_clusters: lower
-// bound on the number of clusters (see pick_clusters).
-inline RowPlan plan_rows(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
-                         int64_t overhead_div, int64_t min_clusters = 1) {
-    RowPlan p{0, 0, 1, 1};
-    if (T <= 0) return p;
+// Blocks of a launch: one per rows_per_step rows, at most max_blocks (the resident blocks wanted).
+inline int64_t grid_blocks(int64_t T, int64_t max_blocks, int rows_per_step) {
     int64_t g = (T + rows_per_step - 1) / rows_per_step;
     if (g > max_blocks) g = max_blocks;
-    if (g < 1) g = 1;
-    int64_t nb = g;
-    if (nseg > 1) {
-        int64_t budget = T / overhead_div - g;
-        if (budget < 0) budget = 0;
-        nb = budget / (nseg - 1);
-        const int64_t want = nseg < min_clusters ? nseg : min_clusters;
-        if (want > 1 && nb > g / want) nb = g / want;
-        if (nb > g) nb = g;
-        if (nb < 1) nb = 1;
-        int64_t pow2 = 1;
-        while (pow2 * 2 <= nb) pow2 *= 2;
-        nb = pow2;
-    }
+    return g < 1 ? 1 : g;
+}
+
+// g blocks in clusters of nb.
+inline RowPlan make_plan(int64_t T, int64_t g, int64_t nb) {
+    RowPlan p{0, 0, 1, 1};
+    if (T <= 0) return p;
     int64_t clusters = (g + nb - 1) / nb;
     const int64_t rpc = (T + clusters - 1) / clusters;
     clusters = (T + rpc - 1) / rpc;
@@ -89,6 +77,68 @@ inline RowPlan plan_rows(int64_t T, int64_t nseg, int64_t max_blocks, int rows_p
     p.rows_per_cluster = rpc;
     p.nb = static_cast<int32_t>(nb);
     return p;
+}
+
+// One cluster: all blocks move through the rows together (nothing changes per segment).
+inline RowPlan plan_rows(int64_t T, int64_t max_blocks, int rows_per_step) {
+    const int64_t g = grid_blocks(T, max_blocks, rows_per_step);
+    return make_plan(T, g, g);
+}
+
+// Forward with per-segment modulation rows: about `want` clusters (see pick_clusters), nb a
+// power of two.
+inline RowPlan plan_rows_clusters(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
+                                  int64_t want) {
+    const int64_t g = grid_blocks(T, max_blocks, rows_per_step);
+    if (nseg <= 1 || want <= 1) return make_plan(T, g, g);
+    int64_t nb = 1;
+    while (nb * 2 * want <= g) nb *= 2;
+    return make_plan(T, g, nb);
+}
+
+// Fraction of the streaming time a backward launch loses when its blocks form C clusters, i.e.
+// move C windows through memory at once instead of one (measured at D = 5120 on 149 760 tokens
+// in equal segments, restarts taken out: 1.2, 2.9, 7.9, 12.4, 15.5 % at C = 2, 4, 8, 16, 32;
+// extrapolated beyond), interpolated in log2 C.
+inline double cluster_penalty(int64_t C) {
+    static const double tab[] = {0.0, 0.012, 0.029, 0.079, 0.124, 0.155, 0.19, 0.22, 0.25};
+    if (C <= 1) return 0.0;
+    if (C >= 256) return tab[8];
+    int lo = 0;
+    while ((int64_t{2} << lo) <= C) ++lo;                    // 2^lo <= C < 2^(lo+1), lo <= 7
+    const double frac = static_cast<double>(C - (int64_t{1} << lo)) / static_cast<double>(int64_t{1} << lo);
+    return tab[lo] + (tab[lo + 1] - tab[lo]) * frac;
+}
+
+// Row plan of a backward that keeps per-(block, segment) partial-sum slots.  With several
+// segments the blocks per cluster nb (a power of two) minimise
+//     stream_us * cluster_penalty(C)                       windows
+//   + (C + nseg) * nb * slot_rows * stream_us / T          slots written and read back
+//   + (nseg / C + 1) * 4 us                                pipeline restarts per block
+// where slot_rows is what one slot costs in units of one row's traffic and stream_us the time
+// the rows take at the streaming rate.
+inline RowPlan plan_rows_slots(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
+                               double stream_us, double slot_rows) {
+    if (T <= 0) return RowPlan{0, 0, 1, 1};
+    const int64_t g = grid_blocks(T, max_blocks, rows_per_step);
+    int64_t nb = g;
+    if (nseg > 1) {
+        double best = 0.0;
+        for (int64_t cand = 1; cand <= g; cand *= 2) {
+            int64_t C = (g + cand - 1) / cand;
+            const int64_t rpc = (T + C - 1) / C;
+            C = (T + rpc - 1) / rpc;
+            const double cost = stream_us * cluster_penalty(C) +
+                                static_cast<double>(C + nseg) * static_cast<double>(cand) * slot_rows *
+                                    stream_us / static_cast<double>(T) +
+                                (static_cast<double>(nseg) / static_cast<double>(C) + 1.0) * 4.0;
+            if (cand == 1 || cost < best) {
+                best = cost;
+                nb = cand;
+            }
+        }
+    }
+    return make_plan(T, g, nb);
 }
 
 // How a row of `nchunks` 16-byte chunks is split: K waves per row, VPL chunks per lane.  A lane
