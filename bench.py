@@ -221,6 +221,18 @@ def main():
 
     if not args.no_extras:
         out["extras"] = extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fwd_ms)
+        # backward that forms the statistics again from x (no mean/rstd kept between the passes),
+        # next to the saved-statistics backward timed the same way (back-to-back launches)
+        def bwd_rc():
+            rc = lnmod.lnmod_backward(dy, x, None, scale, B, S, D, 1e-6, st, None, None, dx, dshift,
+                                      dscale, ws, ws.numel(), BF16, PER_SAMPLE)
+            assert rc == 0, lnmod.lnmod_status_string(rc)
+        sv_ms = _time_ms(torch, stream, bwd, iters=40, warm=5)
+        rc_ms = _time_ms(torch, stream, bwd_rc, iters=40, warm=5)
+        sv2_ms = _time_ms(torch, stream, bwd, iters=40, warm=5)
+        out["extras"]["bwd_recompute_stats"] = {
+            "recompute_us": round(rc_ms * 1e3, 1), "recompute_GBs": _gbs(T * 6 * D, rc_ms),
+            "saved_stats_back_to_back_us": [round(sv_ms * 1e3, 1), round(sv2_ms * 1e3, 1)]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(D, args.cpu_sample_tokens)
     print(json.dumps(out))

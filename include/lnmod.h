@@ -80,7 +80,10 @@ int lnmod_forward(const void* x, const void* shift, const void* scale,
  * Backward (Sec. 3.3, backward: dx, and dshift/dscale by per-feature accumulation along the
  * sequence in fp32).  dy, x, dx: [B*S, D]; mean, rstd: what lnmod_forward saved for this x.
  * `shift` is not needed and may be NULL; `eps` is not needed (rstd is saved) and is only
- * validated.  LNMOD_PER_SAMPLE: dshift, dscale are float32 [B, D] and `workspace` must hold
+ * validated.  mean and rstd may both be NULL (one alone is LNMOD_EINVAL): the statistics are
+ * then formed again from x with `eps`, for callers that keep only x between the passes
+ * (Sec. 3.3: nothing but the operator's output has to be stored); the result agrees with the
+ * saved-statistics result to rounding.  LNMOD_PER_SAMPLE: dshift, dscale are float32 [B, D] and `workspace` must hold
  * lnmod_backward_workspace_bytes(B, B*S, D, mod) bytes (contents need no initialisation and
  * are garbage afterwards).  LNMOD_PER_TOKEN: dshift, dscale are [B, S, D] in the I/O dtype;
  * workspace may be NULL.
@@ -106,7 +109,7 @@ int lnmod_forward_varlen(const void* x, const void* shift, const void* scale,
 /*
  * Backward on a packed batch.  dshift, dscale: float32 [nseg, D]; the rows of zero-length
  * segments are written as zeros.  workspace: lnmod_backward_workspace_bytes(nseg, T, D,
- * LNMOD_PER_SAMPLE) bytes.
+ * LNMOD_PER_SAMPLE) bytes.  mean and rstd may both be NULL, as in lnmod_backward.
  */
 int lnmod_backward_varlen(const void* dy, const void* x, const void* shift, const void* scale,
                           const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D,

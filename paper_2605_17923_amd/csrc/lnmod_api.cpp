@@ -31,11 +31,13 @@ int64_t total_tokens(int64_t B, int64_t S) {
 }
 
 size_t workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
-    // partial-sum slots of the plan with more of them (the dtype is not an argument of the query)
+    // partial-sum slots of the plan with the most of them (neither the dtype nor whether the
+    // statistics will be recomputed is an argument of the query)
     int64_t slots = 0;
-    for (int dtype = 0; dtype < 2; ++dtype) {
+    for (int v = 0; v < 4; ++v) {
+        const int dtype = v & 1;
         if (D % (dtype == 0 ? 8 : 4) != 0) continue;
-        const lnmod::RowPlan pl = lnmod::bwd_plan(T, nseg, D, dtype);
+        const lnmod::RowPlan pl = lnmod::bwd_plan(T, nseg, D, dtype, (v & 2) != 0);
         const int64_t s = lnmod::bwd_slots(pl, nseg);
         if (s > slots) slots = s;
     }
@@ -79,8 +81,8 @@ int backward_impl(const void* dy, const void* x, const void* scale, const int32_
         return LNMOD_OK;
     }
     if (nseg == 0) return LNMOD_EINVAL;
-    if (!dy || !x || !scale || !mean || !rstd || !dx || !dshift || !dscale || (varlen && !cu))
-        return LNMOD_EINVAL;
+    if (!dy || !x || !scale || !dx || !dshift || !dscale || (varlen && !cu)) return LNMOD_EINVAL;
+    if ((mean == nullptr) != (rstd == nullptr)) return LNMOD_EINVAL;    // both, or neither (recompute)
     if (!aligned16(dy) || !aligned16(x) || !aligned16(scale) || !aligned16(dx) ||
         !aligned16(dshift) || !aligned16(dscale))
         return LNMOD_EALIGN;

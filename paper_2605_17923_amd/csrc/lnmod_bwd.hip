@@ -6,19 +6,26 @@
 namespace lnmod {
 namespace {
 
-template <typename Tag, int VPL, int K, int R, bool TOK>
-void go_seg_r(const BwdArgs& a, int64_t blocks, hipStream_t st) {
+template <typename Tag, int VPL, int K, int R, bool TOK, bool RC>
+void go_seg_rc(const BwdArgs& a, int64_t blocks, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks)), block(K * kWave);
     if (a.nchunks == K * VPL * kWave)
-        hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, true, TOK>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, true, TOK, true, RC>), grid, block, 0, st, a);
     else
-        hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, false, TOK>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((bwd_seg_kernel<Tag, VPL, K, R, false, TOK, true, RC>), grid, block, 0, st, a);
 }
 
+// The statistics are recomputed when the caller passed none.
 template <typename Tag, int VPL, int K, bool TOK>
 void go_seg(const BwdArgs& a, int R, int64_t blocks, hipStream_t st) {
-    if (R == 1) go_seg_r<Tag, VPL, K, 1, TOK>(a, blocks, st);
-    else go_seg_r<Tag, VPL, K, 2, TOK>(a, blocks, st);
+    const bool rc = a.mean == nullptr;
+    if (R == 1) {
+        if (rc) go_seg_rc<Tag, VPL, K, 1, TOK, true>(a, blocks, st);
+        else go_seg_rc<Tag, VPL, K, 1, TOK, false>(a, blocks, st);
+    } else {
+        if (rc) go_seg_rc<Tag, VPL, K, 2, TOK, true>(a, blocks, st);
+        else go_seg_rc<Tag, VPL, K, 2, TOK, false>(a, blocks, st);
+    }
 }
 
 // Every (VPL, K) the shape table, the fp32 rule and the per-token rule can ask for.
@@ -88,6 +95,7 @@ BwdArgs make_args(const Problem& p, const void* dy, const void* x, const void* s
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
+    a.eps = p.eps;
     return a;
 }
 
@@ -110,9 +118,10 @@ hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
     return hipGetLastError();
 }
 
-RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute) {
     const int E = dtype == 0 ? 8 : 4;
-    const Shape sh = bwd_shape(static_cast<int>(D / E), dtype);
+    const int nchunks = static_cast<int>(D / E);
+    const Shape sh = recompute ? rc_bwd_shape(nchunks, dtype) : bwd_shape(nchunks, dtype);
     // a row moves 3 D elements (dy, x, dx), a slot 2 D floats that are written and read back
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 3.0 * elem / 5.8e6;
@@ -125,8 +134,9 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
                           float* dscale, float* ws, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
-    const Shape sh = bwd_shape(a.nchunks, p.dtype);
-    const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype);
+    const bool rc = mean == nullptr;
+    const Shape sh = rc ? rc_bwd_shape(a.nchunks, p.dtype) : bwd_shape(a.nchunks, p.dtype);
+    const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype, rc);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)

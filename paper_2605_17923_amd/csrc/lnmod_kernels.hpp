@@ -170,6 +170,15 @@ __device__ inline float wave_sum(float v) {
     return s;
 }
 
+// Sum over lanes 0..15 only (one DPP row), returned to every lane.
+__device__ inline float row0_sum(float v) {
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    v = dpp_add<0x140>(v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+}
+
 // ---- segment table: fixed-length samples (cu == nullptr) or packed offsets on the device ----
 struct Segments {
     const int32_t* cu;   // [nseg+1] token offsets, or nullptr for nseg samples of S tokens
@@ -488,9 +497,18 @@ struct BwdArgs {
     int32_t D;
     int32_t nchunks;
     float inv_D;
+    float eps;               // only read when the statistics are recomputed (RC)
 };
 
-template <typename Tag, int VPL, int K, int R, bool EXACT, bool TOK = false, bool PF = true>
+// RC: mean and rstd are not read but formed again from x, for callers that keep only x between
+// the passes (Sec. 3.3: only the operator's output has to be stored).  Everything a row needs
+// comes out of one pass over the registers and one barrier: every wave takes a pivot c (the
+// mean of the first elements its lanes hold, so that x - c is small against the row's spread)
+// and sums x-c, (x-c)^2, g and g*(x-c); the K waves' numbers are moved to one common pivot c0
+// and added (S1, S2, G1, G2; lane k of every wave takes wave k's), which gives
+//   mean = c0 + S1/D,   sum (x-mean)^2 = S2 - S1^2/D,   sum g (x-mean) = G2 - (S1/D) G1,
+// and the dshift/dscale sums are taken in the second pass, where xhat is rebuilt anyway.
+template <typename Tag, int VPL, int K, int R, bool EXACT, bool TOK = false, bool PF = true, bool RC = false>
 __global__ __launch_bounds__(K* kWave)
 LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, (TOK ? 3 : 2) * (PF ? 2 * R : R) / 2))
 void bwd_seg_kernel(const BwdArgs a) {
@@ -498,6 +516,7 @@ void bwd_seg_kernel(const BwdArgs a) {
     constexpr int E = io::E;
     constexpr int NS = TOK ? 3 : 2;            // streamed inputs per row: dy, x (, scale)
     __shared__ float part[2][R][K][2];
+    __shared__ float stat[RC ? 2 : 1][R][K][RC ? 5 : 1];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -509,6 +528,23 @@ void bwd_seg_kernel(const BwdArgs a) {
     for (int i = 0; i < VPL; ++i) {
         chunk[i] = (i * K + wave) * kWave + lane;
         ok[i] = EXACT || chunk[i] < a.nchunks;
+    }
+    // RC: lane k < K merges wave k's sums and needs the number of features wave k holds; every
+    // wave needs one over the number of its lanes that hold a first chunk
+    float lane_cnt = 0.0f, inv_first = 0.0f;
+    if (RC) {
+        static_assert(K <= 16, "the merge runs on one DPP row");
+        int n = 0;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            int left = a.nchunks - (i * K + lane) * kWave;
+            left = left < 0 ? 0 : left > kWave ? kWave : left;
+            n += left;
+        }
+        lane_cnt = lane < K ? static_cast<float>(n * E) : 0.0f;
+        int first = a.nchunks - wave * kWave;
+        first = first < 1 ? 1 : first > kWave ? kWave : first;
+        inv_first = 1.0f / static_cast<float>(first);
     }
 
     const int64_t cluster = blockIdx.x / a.nb;
@@ -552,8 +588,8 @@ void bwd_seg_kernel(const BwdArgs a) {
             for (int j = 0; j < R; ++j) {
                 const int64_t row = base + j;
                 const bool live = row < stop;
-                qmu[j] = live ? a.mean[row] : 0.0f;
-                qrs[j] = live ? a.rstd[row] : 0.0f;
+                qmu[j] = !RC && live ? a.mean[row] : 0.0f;
+                qrs[j] = !RC && live ? a.rstd[row] : 0.0f;
 #pragma unroll
                 for (int i = 0; i < VPL; ++i) {
                     if (live && ok[i]) {
@@ -586,62 +622,142 @@ void bwd_seg_kernel(const BwdArgs a) {
             // xhat and g are not kept: they are rebuilt from the packed registers in pass 2,
             // which costs a few ALU operations and saves the registers the prefetch needs.
             float c1[R], c2[R];
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                float p1 = 0.0f, p2 = 0.0f;
-#pragma unroll
-                for (int i = 0; i < VPL; ++i) {
-                    float dyv[E], xv[E], scv[E];
-                    io::unpack(raw[0][j][i], dyv);
-                    io::unpack(raw[1][j][i], xv);
-                    if (TOK) io::unpack(raw[NS - 1][j][i], scv);
-#pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        // xhat as (x - mean) * rstd, not x*rstd - mean*rstd: the latter loses every digit
-                        // on (near-)constant rows, where rstd is as large as 1/sqrt(eps)
-                        const float h = (xv[e] - mu[j]) * rs[j];
-                        const float gg = dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e]);
-                        p1 += gg;
-                        p2 += gg * h;
-                        if (!TOK) {
-                            acc_s[i][e] += dyv[e];
-                            acc_c[i][e] += dyv[e] * h;
-                        }
-                    }
-                    if (!TOK) {
-                        // Pin the running sums here.  They are only consumed at the end of the loop,
-                        // so the optimiser would otherwise sink these adds below the barrier and keep
-                        // every unpacked dy and xhat alive until then (twice the row in registers).
-#pragma unroll
-                        for (int e = 0; e < E; ++e) asm volatile("" : "+v"(acc_s[i][e]), "+v"(acc_c[i][e]));
-                    }
-                    // one chunk at a time: stops the scheduler from unpacking every chunk up front
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                c1[j] = wave_sum(p1);
-                c2[j] = wave_sum(p2);
-            }
-            if (K > 1) {
-                if (lane == 0) {
-#pragma unroll
-                    for (int j = 0; j < R; ++j) {
-                        part[buf][j][wave][0] = c1[j];
-                        part[buf][j][wave][1] = c2[j];
-                    }
-                }
-                __syncthreads();
+            if constexpr (RC) {
+                // one pass: pivot, then the four sums of this wave's part of each row
+                float piv[R], s1[R], s2[R];
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    float t1 = 0.0f, t2 = 0.0f;
-#pragma unroll
-                    for (int w = 0; w < K; ++w) {
-                        t1 += part[buf][j][w][0];
-                        t2 += part[buf][j][w][1];
+                    {
+                        float v0[E];
+                        io::unpack(raw[1][j][0], v0);
+                        piv[j] = wave_sum(v0[0]) * inv_first;
                     }
-                    c1[j] = t1;
-                    c2[j] = t2;
+                    float t1 = 0.0f, t2 = 0.0f, p1 = 0.0f, p2 = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < VPL; ++i) {
+                        float dyv[E], xv[E], scv[E];
+                        io::unpack(raw[0][j][i], dyv);
+                        io::unpack(raw[1][j][i], xv);
+                        if (TOK) io::unpack(raw[NS - 1][j][i], scv);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            const float xp = xv[e] - piv[j];
+                            const float gg = dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e]);
+                            p1 += gg;
+                            p2 += gg * xp;              // dead chunks: dy = 0, so gg = 0
+                            if (ok[i]) {
+                                t1 += xp;
+                                t2 += xp * xp;
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    s1[j] = wave_sum(t1);
+                    s2[j] = wave_sum(t2);
+                    c1[j] = wave_sum(p1);
+                    c2[j] = wave_sum(p2);
                 }
-                buf ^= 1;
+                if (K > 1) {
+                    if (lane == 0) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j) {
+                            stat[buf][j][wave][0] = piv[j];
+                            stat[buf][j][wave][1] = s1[j];
+                            stat[buf][j][wave][2] = s2[j];
+                            stat[buf][j][wave][3] = c1[j];
+                            stat[buf][j][wave][4] = c2[j];
+                        }
+                    }
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    // lane k < K moves wave k's sums to the first wave's pivot c0 (e = c_k - c0 is
+                    // small); adding them over the lanes gives
+                    //   S1 = sum (x-c0), S2 = sum (x-c0)^2, G1 = sum g, G2 = sum g (x-c0)
+                    float c0 = piv[j], S1 = s1[j], S2 = s2[j], G1 = c1[j], G2 = c2[j];
+                    if (K > 1) {
+                        c0 = stat[buf][j][0][0];
+                        float e = 0.0f, a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f;
+                        if (lane < K) {
+                            e = stat[buf][j][lane][0] - c0;
+                            a1 = stat[buf][j][lane][1];
+                            a2 = stat[buf][j][lane][2];
+                            b1 = stat[buf][j][lane][3];
+                            b2 = stat[buf][j][lane][4];
+                        }
+                        S1 = row0_sum(a1 + lane_cnt * e);
+                        S2 = row0_sum(a2 + e * (2.0f * a1 + lane_cnt * e));
+                        G1 = row0_sum(b1);
+                        G2 = row0_sum(b2 + e * b1);
+                    }
+                    const float dm = S1 / static_cast<float>(a.D);       // mean - c0
+                    float m2 = S2 - dm * S1;
+                    m2 = m2 > 0.0f ? m2 : 0.0f;
+                    mu[j] = c0 + dm;
+                    rs[j] = 1.0f / sqrtf(m2 * a.inv_D + a.eps);
+                    c1[j] = G1;
+                    c2[j] = (G2 - dm * G1) * rs[j];
+                }
+                if (K > 1) buf ^= 1;
+            } else {
+    #pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    float p1 = 0.0f, p2 = 0.0f;
+    #pragma unroll
+                    for (int i = 0; i < VPL; ++i) {
+                        float dyv[E], xv[E], scv[E];
+                        io::unpack(raw[0][j][i], dyv);
+                        io::unpack(raw[1][j][i], xv);
+                        if (TOK) io::unpack(raw[NS - 1][j][i], scv);
+    #pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            // xhat as (x - mean) * rstd, not x*rstd - mean*rstd: the latter loses every digit
+                            // on (near-)constant rows, where rstd is as large as 1/sqrt(eps)
+                            const float h = (xv[e] - mu[j]) * rs[j];
+                            const float gg = dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e]);
+                            p1 += gg;
+                            p2 += gg * h;
+                            if (!TOK) {
+                                acc_s[i][e] += dyv[e];
+                                acc_c[i][e] += dyv[e] * h;
+                            }
+                        }
+                        if (!TOK) {
+                            // Pin the running sums here.  They are only consumed at the end of the loop,
+                            // so the optimiser would otherwise sink these adds below the barrier and keep
+                            // every unpacked dy and xhat alive until then (twice the row in registers).
+    #pragma unroll
+                            for (int e = 0; e < E; ++e) asm volatile("" : "+v"(acc_s[i][e]), "+v"(acc_c[i][e]));
+                        }
+                        // one chunk at a time: stops the scheduler from unpacking every chunk up front
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    c1[j] = wave_sum(p1);
+                    c2[j] = wave_sum(p2);
+                }
+                if (K > 1) {
+                    if (lane == 0) {
+    #pragma unroll
+                        for (int j = 0; j < R; ++j) {
+                            part[buf][j][wave][0] = c1[j];
+                            part[buf][j][wave][1] = c2[j];
+                        }
+                    }
+                    __syncthreads();
+    #pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        float t1 = 0.0f, t2 = 0.0f;
+    #pragma unroll
+                        for (int w = 0; w < K; ++w) {
+                            t1 += part[buf][j][w][0];
+                            t2 += part[buf][j][w][1];
+                        }
+                        c1[j] = t1;
+                        c2[j] = t2;
+                    }
+                    buf ^= 1;
+                }
             }
             // pass 2: dx = rstd * (g - c1 - xhat*c2).  The empty asm makes the packed registers
             // opaque so that common-subexpression elimination cannot carry pass 1's fp32 values
@@ -671,6 +787,10 @@ void bwd_seg_kernel(const BwdArgs a) {
                                 const float h = (xv[e] - mu[j]) * rs[j];
                                 o[e] = (dyv[e] * (TOK ? 1.0f + scv[e] : A[i][e])) * rs[j] - k1 - h * k2;
                                 if (TOK) ds[e] = dyv[e] * h;
+                                if (RC && !TOK) {
+                                    acc_s[i][e] += dyv[e];
+                                    acc_c[i][e] += dyv[e] * h;
+                                }
                             }
                             const uint32_t lo = static_cast<uint32_t>(chunk[i]) * 16u;
                             store16_u(a.dx, row * row_bytes, lo, io::pack(o));

@@ -233,6 +233,33 @@ inline Shape bwd_shape(int nchunks, int dtype) {
     return {sp.K, sp.VPL, 2, per_cu};
 }
 
+// Backward that forms the statistics again from x.  It has one more dependent chain per step
+// (pivot, four wave sums, the merge with a division and a square root), which fewer waves per
+// row with more chunks each, or two blocks per CU, hide better than the shapes above; timed at
+// D = 512 ... 8192 on 75 600 tokens, where it then runs within 1 to 6 % of the backward that
+// reads the saved statistics (D = 2048: 14 %).
+inline Shape rc_bwd_shape(int nchunks, int dtype) {
+    if (dtype == 0) {
+        const int cols = (nchunks + 63) / 64;
+        switch (cols) {
+            case 1:
+            case 2: break;
+            case 3: return {1, 3, 2, 4};
+            case 4: return {2, 2, 2, 4};
+            case 5: return {3, 2, 2, 3};
+            case 6: return {3, 2, 2, 2};
+            case 7: return {4, 2, 1, 2};
+            case 8: return {4, 2, 2, 1};
+            case 9:
+            case 10: return {4, 3, 1, 2};
+            case 11:
+            case 12: return {4, 3, 2, 1};
+            default: return {8, 2, 2, 1};
+        }
+    }
+    return bwd_shape(nchunks, dtype);
+}
+
 // Per-token modulation (three input streams forward; three in, three out backward).  The rule:
 // the split of choose_split, one row per step for shared rows of 4 KB and more (backward) or
 // always (forward), about ten waves per CU.  For bf16 the widths that were timed (same procedure
@@ -279,7 +306,7 @@ inline Shape tok_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
 
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
 // kernel's grid and tells the second pass which partial-sum slots belong to a segment.
-RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute);
 inline int64_t bwd_slots(const RowPlan& p, int64_t nseg) { return (p.clusters + nseg) * p.nb; }
 
 // Shape of the second pass: V features per lane, W waves per block.  Wide lanes need enough

@@ -222,7 +222,8 @@ def workspace(B_or_nseg, total_tokens, D, device):
 
 
 def backward(dy, x, scale, mean, rstd, eps=1e-6, stream=None, ws=None):
-    """-> dx, dshift, dscale (float32 [B,D] per sample; I/O dtype [B,S,D] per token)."""
+    """-> dx, dshift, dscale (float32 [B,D] per sample; I/O dtype [B,S,D] per token).
+    mean = rstd = None: the statistics are formed again from x with eps."""
     import torch
     B, S, D = x.shape
     mod = LNMOD_PER_TOKEN if scale.dim() == 3 else LNMOD_PER_SAMPLE

@@ -21,8 +21,9 @@ def _gpu():
     torch.cuda.synchronize()
 
 
-def run_case(inp, check_bwd=True, sample_rows=None, label=""):
-    """Forward (+ backward) of one workload through the C ABI, checked against the oracle."""
+def run_case(inp, check_bwd=True, sample_rows=None, label="", recompute=False):
+    """Forward (+ backward) of one workload through the C ABI, checked against the oracle.
+    recompute: the backward gets no saved statistics and forms them again from x."""
     w = inp.workload
     dt = w.dtype
     T, D, B = inp.T, inp.D, inp.B
@@ -77,12 +78,14 @@ def run_case(inp, check_bwd=True, sample_rows=None, label=""):
         return
     dy = to_device(inp.dy, dt)
     if w.varlen:
-        dx, dsh, dsc = lnmod.backward_varlen(dy, x, scale, cu_dev, mean, rstd, w.eps)
+        dx, dsh, dsc = lnmod.backward_varlen(dy, x, scale, cu_dev, None if recompute else mean,
+                                             None if recompute else rstd, w.eps)
     else:
         S = inp.S
         dx, dsh, dsc = lnmod.backward(dy.view(B, S, D), x.view(B, S, D),
                                       scale.view(B, S, D) if per_token else scale,
-                                      mean.reshape(B, S), rstd.reshape(B, S), w.eps)
+                                      None if recompute else mean.reshape(B, S),
+                                      None if recompute else rstd.reshape(B, S), w.eps)
     torch.cuda.synchronize()
     dx64, dsh64, dsc64 = oracle.backward(inp.dy, inp.x, inp.scale, w.eps, cu=cu64, mod=omod)
     check_io_tensor("dx", dx.reshape(T, D)[rows_t], dx64[rows], dt)
@@ -188,6 +191,36 @@ def test_constant_rows_and_large_offsets():
     run_case(inp, label="degenerate rows")
 
 
+# ---- backward without saved statistics (recomputed from x) --------------------------------------
+@pytest.mark.parametrize("cfg,kw", [(0, {}), (1, dict(S=2111, with_dy=True)), (2, dict(S=1237)), (3, dict(B=2, S=301)),
+                                    (4, dict(lengths=[0, 301, 1, 0, 977, 64, 3, 0]))])
+def test_recompute_backward_reduced_configs(cfg, kw):
+    run_case(synth.make_inputs(cfg, **kw), label="recompute cfg %d" % cfg, recompute=True)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 8), ("bf16", 520), ("bf16", 1024), ("bf16", 1536), ("bf16", 2048),
+                                     ("bf16", 2816), ("bf16", 3072), ("bf16", 4096), ("bf16", 4616), ("bf16", 5120),
+                                     ("bf16", 6144), ("bf16", 7000), ("bf16", 8192),
+                                     ("f32", 8), ("f32", 100), ("f32", 1024), ("f32", 3076), ("f32", 5120),
+                                     ("f32", 8192)])
+def test_recompute_backward_hidden_sizes(dtype, D):
+    run_case(synth.make_inputs(0, B=3, S=45, D=D, dtype=dtype), label="recompute D=%d %s" % (D, dtype),
+             recompute=True)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 1536), ("bf16", 8192), ("f32", 100), ("f32", 6144)])
+def test_recompute_backward_per_token(dtype, D):
+    run_case(synth.make_inputs(3, B=2, S=67, D=D, dtype=dtype), label="recompute per-token D=%d %s" % (D, dtype),
+             recompute=True)
+
+
+def test_recompute_backward_degenerate_rows():
+    inp = synth.make_inputs(0, B=1, S=8, D=1536, dtype="f32")
+    inp.x[0, :] = 3.25
+    inp.x[1, :] += 30.0
+    run_case(inp, label="recompute degenerate rows", recompute=True)
+
+
 # ---- full-size workloads in the benchmark's launch configuration --------------------------------
 def _sample_rows(T, cu, n=1500, seed=7):
     rng = np.random.default_rng(seed)
@@ -208,6 +241,11 @@ def test_config1_full_size():
 def test_config2_full_size():
     inp = synth.make_inputs(2)
     run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+def test_config2_full_size_recompute_backward():
+    inp = synth.make_inputs(2)
+    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens), recompute=True)
 
 
 def test_config3_full_size():
@@ -368,6 +406,16 @@ def test_every_supported_hidden_size_launches():
                 if rc1 != 0 or rc2 != 0:
                     bad.append((D, mod, rc1, rc2))
                     continue
+                # the same backward without saved statistics (recomputed from x) must launch too and
+                # give the same dx to rounding
+                dx2 = torch.empty_like(dx)
+                rc3 = lnmod.lnmod_backward(dy, x, None, scm, B, S, D, 1e-6, st, None, None, dx2, o1, o2, ws,
+                                           ws.numel(), code, mod)
+                if rc3 != 0:
+                    bad.append((D, mod, "recompute", rc3))
+                    continue
+                if D % 40 == 0:
+                    assert float((dx2.double() - dx.double()).abs().max()) <= tol * float(dx.abs().max() + 1), (D, mod)
                 if D % 136 == 0 or D in (8, 8192):        # spot-check the numbers
                     xd, dyd, scd, shd = x.double(), dy.double(), sc.double(), sh.double()
                     mu = xd.mean(1, keepdim=True)
