@@ -221,6 +221,35 @@ def test_recompute_backward_degenerate_rows():
     run_case(inp, label="recompute degenerate rows", recompute=True)
 
 
+# ---- random shapes --------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(seed):
+    # token count, hidden size, layout (fixed / packed / per token), I/O type and whether the
+    # backward gets saved statistics, all drawn from the seed: shapes nobody tuned for
+    rng = np.random.default_rng(1000 + seed)
+    dtype = ("bf16", "f32")[int(rng.integers(0, 2))]
+    step = 8 if dtype == "bf16" else 4
+    D = int(rng.integers(1, 8192 // step + 1)) * step
+    budget = 600_000                                   # elements the oracle handles in a second or two
+    kind = int(rng.integers(0, 3))
+    recompute = bool(rng.integers(0, 2))
+    if kind == 0:                                      # fixed length, per sample
+        B = int(rng.integers(1, 9))
+        S = max(1, int(rng.integers(1, max(2, budget // (B * D) + 1))))
+        inp = synth.make_inputs(2, B=B, S=S, D=D, dtype=dtype, seed=seed)
+    elif kind == 1:                                    # packed segments, some of them empty
+        nseg = int(rng.integers(1, 20))
+        T = max(1, budget // D)
+        cuts = np.sort(rng.integers(0, T + 1, nseg - 1))
+        lengths = np.diff(np.concatenate(([0], cuts, [T]))).tolist()
+        inp = synth.make_inputs(4, lengths=lengths, D=D, dtype=dtype, seed=seed)
+    else:                                              # per token
+        B = int(rng.integers(1, 4))
+        S = max(1, int(rng.integers(1, max(2, budget // (2 * B * D) + 1))))
+        inp = synth.make_inputs(3, B=B, S=S, D=D, dtype=dtype, seed=seed)
+    run_case(inp, label="random seed %d kind %d recompute %d" % (seed, kind, recompute), recompute=recompute)
+
+
 # ---- full-size workloads in the benchmark's launch configuration --------------------------------
 def _sample_rows(T, cu, n=1500, seed=7):
     rng = np.random.default_rng(seed)
