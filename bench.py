@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # by the same counter's reading for lnmod_copy of known size (FETCH_SIZE reads half the loaded
 # bytes, WRITE_SIZE the stored bytes); the runs and readings are in
 # profiles/wan14b_fwd_bwd_pmc_hbm_traffic.md.  Backward = main kernel + second pass.
-MEASURED_TRAFFIC_BYTES = {"forward": 1550959399, "backward": 2348563709}
+MEASURED_TRAFFIC_BYTES = {"forward": 1550957963, "backward": 2348568104}
 
 
 def algorithmic_bytes(T, D, elem):
