@@ -220,7 +220,7 @@ def main():
     }
 
     if not args.no_extras:
-        out["extras"] = extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fwd_ms)
+        out["extras"] = extras(lnmod, torch, x, dy, y, shift, scale, mean, rstd, T, D, st, stream, fwd_ms)
         # backward that forms the statistics again from x (no mean/rstd kept between the passes),
         # next to the saved-statistics backward timed the same way (back-to-back launches)
         def bwd_rc():
@@ -399,7 +399,7 @@ def _run_qknorm(lnmod, torch, stream, st, dev, T, D, iters=20):
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
 
 
-def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
+def extras(lnmod, torch, x, dy, y, shift, scale, mean, rstd, T, D, st, stream, fused_fwd_ms):
     """Context figures: a plain copy as the practical bandwidth ceiling, the unfused two-kernel
     forward (LayerNorm -> xhat in HBM -> modulate), the other workload shapes and the token
     counts of the paper's kernel table (Table 2: N = 8k ... 64k) at D = 5120."""
@@ -408,6 +408,12 @@ def extras(lnmod, torch, x, y, shift, scale, mean, rstd, T, D, st, stream, fused
     nbytes = x.numel() * 2
     ms = _time_ms(torch, stream, lambda: lnmod.lnmod_copy(x, y, nbytes, st))
     res["copy_ceiling_GBs"] = _gbs(2 * nbytes, ms)
+    # the directions taken apart: two reads + one write (the backward's mixture), reads only, writes only
+    ms_a = _time_ms(torch, stream, lambda: lnmod.lnmod_stream_probe(x, dy, y, nbytes, lnmod.LNMOD_PROBE_ADD, st))
+    ms_r = _time_ms(torch, stream, lambda: lnmod.lnmod_stream_probe(x, None, mean, nbytes, lnmod.LNMOD_PROBE_READ, st))
+    ms_w = _time_ms(torch, stream, lambda: lnmod.lnmod_stream_probe(None, None, y, nbytes, lnmod.LNMOD_PROBE_WRITE, st))
+    res["stream_ceilings_GBs"] = {"two_reads_one_write": _gbs(3 * nbytes, ms_a), "read_only": _gbs(nbytes, ms_r),
+                                  "write_only": _gbs(nbytes, ms_w)}
     tmp = torch.empty_like(x)
     ms_u = _time_ms(torch, stream, lambda: lnmod.lnmod_unfused_forward(
         x, shift, scale, 1, T, D, 1e-6, st, tmp, y, mean, rstd, lnmod.LNMOD_BF16))

@@ -145,6 +145,18 @@ int lnmod_unfused_forward(const void* x, const void* shift, const void* scale,
 int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
+ * lnmod_stream_probe: the same access pattern with the directions taken apart, to show what
+ * the memory system gives to reads, to writes and to their mixture (the fused kernels are
+ * compared with these, not only with the data-sheet peak).  a, b, c: `bytes` bytes each
+ * (a multiple of 16; a tail shorter than one 4 KB or 8 KB piece is left out).
+ *   LNMOD_PROBE_ADD    c = a + b in 32-bit lanes: two reads and one write, the backward's mixture
+ *   LNMOD_PROBE_READ   a is read (b unused, may be NULL); c needs 1 KB and is normally not written
+ *   LNMOD_PROBE_WRITE  c is filled with a position-dependent pattern (a, b unused, may be NULL)
+ */
+typedef enum { LNMOD_PROBE_ADD = 1, LNMOD_PROBE_READ = 2, LNMOD_PROBE_WRITE = 3 } lnmod_probe_mode;
+int lnmod_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, void* stream);
+
+/*
  * Gated residual + LayerNorm-Modulate: the "Gate + Norm" chain the paper lists among its fused
  * operators (Sec. 4.4) without defining it; defined here as a DiT block with adaptive LayerNorm
  * has it around every LayerNorm-Modulate (Sec. 3.3):

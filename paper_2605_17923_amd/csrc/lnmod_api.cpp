@@ -342,4 +342,16 @@ int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream) {
     return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
 }
 
+int lnmod_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, void* stream) {
+    if (mode != LNMOD_PROBE_ADD && mode != LNMOD_PROBE_READ && mode != LNMOD_PROBE_WRITE) return LNMOD_EINVAL;
+    if (bytes == 0) return LNMOD_OK;
+    if (bytes % 16 != 0 || !c) return LNMOD_EINVAL;
+    if (mode != LNMOD_PROBE_WRITE && !a) return LNMOD_EINVAL;
+    if (mode == LNMOD_PROBE_ADD && !b) return LNMOD_EINVAL;
+    if (mode == LNMOD_PROBE_READ && bytes < 1024) return LNMOD_EINVAL;       // c must hold 1 KB
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return LNMOD_EALIGN;
+    const hipError_t e = lnmod::launch_stream_probe(a, b, c, bytes, mode, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
 }  // extern "C"

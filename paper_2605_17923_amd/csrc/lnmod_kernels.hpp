@@ -947,4 +947,57 @@ __global__ __launch_bounds__(kCopyWaves* kWave) void copy16_kernel(const u32x4* 
     }
 }
 
+// One-directional and two-read streams in the same pattern, to split the copy figure into what
+// the memory system gives to reads, to writes and to their mixtures.
+//   kProbeAdd    c = a + b per 32-bit lane (two reads, one write: the backward's mixture)
+//   kProbeRead   a is read and summed; the sum is stored only if it equals a value it cannot
+//                take for the fill patterns used, which keeps the loads alive
+//   kProbeWrite  c is filled with a pattern that depends on the position
+constexpr int kProbeAdd = 1, kProbeRead = 2, kProbeWrite = 3;
+
+template <int MODE, int W, int V>
+__global__ __launch_bounds__(W* kWave) void stream_probe_kernel(const u32x4* __restrict__ a,
+                                                               const u32x4* __restrict__ b,
+                                                               u32x4* __restrict__ c, int64_t nvec) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int64_t kPiece = static_cast<int64_t>(V) * kWave;
+    const int64_t pieces = nvec / kPiece;                 // a tail shorter than one piece is left out
+    const int64_t step = static_cast<int64_t>(gridDim.x) * W;
+    auto fetch = [&](int64_t piece, u32x4 (&qa)[V], u32x4 (&qb)[V]) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const bool live = piece < pieces;
+            qa[i] = u32x4{0u, 0u, 0u, 0u};
+            qb[i] = u32x4{0u, 0u, 0u, 0u};
+            if (MODE != kProbeWrite && live) qa[i] = __builtin_nontemporal_load(a + piece * kPiece + i * kWave + lane);
+            if (MODE == kProbeAdd && live) qb[i] = __builtin_nontemporal_load(b + piece * kPiece + i * kWave + lane);
+        }
+    };
+    int64_t piece = static_cast<int64_t>(blockIdx.x) * W + wave;
+    u32x4 ca[V], cb[V], acc = u32x4{0u, 0u, 0u, 0u};
+    fetch(piece, ca, cb);
+    for (; piece < pieces; piece += step) {
+        u32x4 na[V], nb[V];
+        fetch(piece + step, na, nb);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            if (MODE == kProbeRead) {
+                acc += ca[i];
+            } else {
+                const u32x4 v = MODE == kProbeWrite ? u32x4{1u, 2u, static_cast<uint32_t>(i), static_cast<uint32_t>(piece)}
+                                                    : ca[i] + cb[i];
+                __builtin_nontemporal_store(v, c + piece * kPiece + i * kWave + lane);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            ca[i] = na[i];
+            cb[i] = nb[i];
+        }
+    }
+    if (MODE == kProbeRead && acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) c[lane] = acc;
+}
+
 }  // namespace lnmod

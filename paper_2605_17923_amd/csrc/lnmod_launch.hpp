@@ -343,6 +343,7 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
 hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* xhat, void* y, float* mean, float* rstd, hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+hipError_t launch_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, hipStream_t st);
 
 // Gated residual + LayerNorm-Modulate (per-sample / per-segment gate, shift, scale).
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);

@@ -15,13 +15,14 @@ import os
 LNMOD_OK, LNMOD_EINVAL, LNMOD_EUNSUPPORTED, LNMOD_EALIGN, LNMOD_EWORKSPACE, LNMOD_ELAUNCH = range(6)
 LNMOD_BF16, LNMOD_F32 = 0, 1
 LNMOD_PER_SAMPLE, LNMOD_PER_TOKEN = 0, 1
+LNMOD_PROBE_ADD, LNMOD_PROBE_READ, LNMOD_PROBE_WRITE = 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(_HERE, "liblnmod.so")
 
 EXPORTS = ("lnmod_forward", "lnmod_backward", "lnmod_forward_varlen", "lnmod_backward_varlen",
            "lnmod_backward_workspace_bytes", "lnmod_status_string", "lnmod_unfused_forward",
-           "lnmod_copy", "lnmod_gated_forward", "lnmod_gated_backward",
+           "lnmod_copy", "lnmod_stream_probe", "lnmod_gated_forward", "lnmod_gated_backward",
            "lnmod_gated_backward_workspace_bytes", "lnmod_gate_residual", "lnmod_qknorm_forward",
            "lnmod_qknorm_backward", "lnmod_qknorm_backward_workspace_bytes")
 
@@ -63,6 +64,8 @@ def library() -> ctypes.CDLL:
     lib.lnmod_unfused_forward.argtypes = [vp, vp, vp, i64, i64, i64, f32, vp, vp, vp, vp, vp, cint]
     lib.lnmod_copy.restype = cint
     lib.lnmod_copy.argtypes = [vp, vp, sz, vp]
+    lib.lnmod_stream_probe.restype = cint
+    lib.lnmod_stream_probe.argtypes = [vp, vp, vp, sz, cint, vp]
     lib.lnmod_gated_forward.restype = cint
     lib.lnmod_gated_forward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp,
                                         vp, vp, vp, vp, cint]
@@ -143,6 +146,10 @@ def lnmod_unfused_forward(x, shift, scale, B, S, D, eps, stream, xhat_tmp, y, me
 
 def lnmod_copy(src, dst, nbytes, stream):
     return library().lnmod_copy(_p(src), _p(dst), nbytes, stream)
+
+
+def lnmod_stream_probe(a, b, c, nbytes, mode, stream):
+    return library().lnmod_stream_probe(_p(a), _p(b), _p(c), nbytes, mode, stream)
 
 
 def lnmod_gated_forward(x, u, gate, shift, scale, cu_seqlens, B_or_nseg, S_or_T, D, eps, stream,

@@ -144,6 +144,15 @@ def test_copy_and_unfused_reject_bad_arguments(lib):
     assert lnmod.lnmod_copy(A, A, 60, None) == lnmod.LNMOD_EINVAL
     assert lnmod.lnmod_copy(A + 4, A, 64, None) == lnmod.LNMOD_EALIGN
     assert lnmod.lnmod_copy(A, A, 0, None) == lnmod.LNMOD_OK
+    probe = lnmod.lnmod_stream_probe
+    assert probe(A, A, A, 4096, 0, None) == lnmod.LNMOD_EINVAL                 # no such mode
+    assert probe(A, None, A, 4096, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EINVAL
+    assert probe(None, None, A, 4096, lnmod.LNMOD_PROBE_READ, None) == lnmod.LNMOD_EINVAL
+    assert probe(A, None, A, 512, lnmod.LNMOD_PROBE_READ, None) == lnmod.LNMOD_EINVAL
+    assert probe(None, None, None, 4096, lnmod.LNMOD_PROBE_WRITE, None) == lnmod.LNMOD_EINVAL
+    assert probe(A, A, A, 4100, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EINVAL
+    assert probe(A, A, A + 8, 4096, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EALIGN
+    assert probe(None, None, None, 0, lnmod.LNMOD_PROBE_WRITE, None) == lnmod.LNMOD_OK
     u = lnmod.lnmod_unfused_forward
     assert u(A, A, A, 2, 4, 64, 1e-6, None, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
     assert u(A, A, A, 2, 4, 63, 1e-6, None, A, A, A, A, 0) == lnmod.LNMOD_EUNSUPPORTED

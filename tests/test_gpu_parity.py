@@ -362,6 +362,31 @@ def test_unfused_comparator_and_copy_match():
     assert torch.equal(dst, x)
 
 
+def test_stream_probes_move_what_they_say():
+    st = torch.cuda.current_stream().cuda_stream
+    n = 3 * 1024 * 1024 + 4096 + 48                    # bytes: whole pieces plus a tail that is left out
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    a = torch.randint(0, 2 ** 31 - 1, (n // 4,), generator=g, device="cuda", dtype=torch.int32)
+    b = torch.randint(0, 2 ** 31 - 1, (n // 4,), generator=g, device="cuda", dtype=torch.int32)
+    c = torch.full((n // 4,), -7, device="cuda", dtype=torch.int32)
+    assert lnmod.lnmod_stream_probe(a, b, c, n, lnmod.LNMOD_PROBE_ADD, st) == 0
+    torch.cuda.synchronize()
+    whole = (n // 4096) * 4096 // 4                     # 4 KB pieces
+    assert torch.equal(c[:whole], a[:whole] + b[:whole])            # int32 wraps like the 32-bit lanes
+    assert bool((c[whole:] == -7).all())
+    c.fill_(-7)
+    assert lnmod.lnmod_stream_probe(a, None, c, n, lnmod.LNMOD_PROBE_READ, st) == 0
+    torch.cuda.synchronize()
+    assert bool((c == -7).all())                        # the read probe stores nothing
+    assert lnmod.lnmod_stream_probe(None, None, c, n, lnmod.LNMOD_PROBE_WRITE, st) == 0
+    torch.cuda.synchronize()
+    whole8 = (n // 8192) * 8192 // 4                    # 8 KB pieces
+    w = c[:whole8].view(-1, 4)
+    assert bool((w[:, 0] == 1).all()) and bool((w[:, 1] == 2).all())
+    assert bool((c[whole8:] == -7).all())
+
+
 def test_calls_can_be_captured_in_a_hip_graph():
     # the library allocates nothing, never synchronises and records no memset: a forward +
     # backward pair captured into a HIP graph must replay to the eager results every time, also
