@@ -468,9 +468,9 @@ def test_every_supported_hidden_size_launches():
                 if rc3 != 0:
                     bad.append((D, mod, "recompute", rc3))
                     continue
-                if D % 40 == 0:
+                if True:
                     assert float((dx2.double() - dx.double()).abs().max()) <= tol * float(dx.abs().max() + 1), (D, mod)
-                if D % 136 == 0 or D in (8, 8192):        # spot-check the numbers
+                if True:                                  # every size: a shape that does not cover its row shows here
                     xd, dyd, scd, shd = x.double(), dy.double(), sc.double(), sh.double()
                     mu = xd.mean(1, keepdim=True)
                     r = 1.0 / torch.sqrt(((xd - mu) ** 2).mean(1, keepdim=True) + 1e-6)
