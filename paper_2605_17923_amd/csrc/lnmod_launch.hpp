@@ -165,12 +165,14 @@ inline Split choose_split(int nchunks, int dtype) {
 
 // Launch shape of the per-sample / per-segment kernels: K waves per row, VPL chunks per lane, R
 // rows per block and step, per_cu resident blocks per CU.  For bf16 the shape comes from a table
-// indexed by the row length in units of 64 chunks (512 features).  The table was measured, not
-// derived: every (K, VPL, R, per_cu) with at most 25 % padding and 3 to 16 waves per CU was timed
-// on one sample of about 770 MB per tensor at D = 1152 ... 8192, three times on different
-// machines, and the entry is the shape with the best worst run.  What the winners share: a wave
-// count that is a multiple of the four SIMDs of a CU (or a single block of 5 or 6 waves), and
-// 16 to 32 KB of row data in flight per CU.  fp32 keeps the rule-based split.
+// indexed by the row length in units of 64 chunks (512 features).  The tables were measured, not
+// derived: every instantiated (K, VPL, R, per_cu) that covers the row with at most 60 % padding
+// and 3 to 16 waves per CU was timed on one sample of about 770 MB per tensor at every multiple of
+// 512 features from 512 to 8192 (the widths of the models of Sec. 4.1, D = 1536 and 5120, three
+// times on different machines, the others twice), and the entry is the shape with the best worst
+// run.  What the winners share: a wave count that is a multiple of the four SIMDs of a CU (or a
+// single block of 5 or 6 waves), and 16 to 32 KB of row data in flight per CU.  Neighbouring
+// widths do not share winners: an entry that is best at D = 4096 loses 28 % at D = 3584.
 struct Shape {
     int K;
     int VPL;
@@ -180,24 +182,17 @@ struct Shape {
 
 inline Shape fwd_shape(int nchunks, int dtype) {
     if (dtype == 0) {
+        static const Shape tab[17] = {
+            {1, 1, 2, 8},                                                    // (unused)
+            {1, 1, 2, 8}, {1, 2, 2, 4}, {1, 3, 1, 8}, {2, 2, 1, 4},          // D <=  512 ... 2048
+            {2, 3, 1, 4}, {4, 2, 1, 3}, {4, 2, 1, 3}, {4, 2, 2, 1},          //      2560 ... 4096
+            {4, 3, 1, 2}, {5, 2, 2, 1}, {4, 3, 1, 2}, {4, 3, 1, 2},          //      4608 ... 6144
+            {6, 3, 1, 2}, {6, 3, 1, 2}, {6, 3, 1, 1}, {6, 3, 1, 1}};         //      6656 ... 8192
         const int cols = (nchunks + 63) / 64;
-        switch (cols) {
-            case 1: return {1, 1, 2, 4};
-            case 2: return {1, 2, 2, 4};
-            // D = 1536: three blocks per CU are 3 % faster on 126 000 rows, four are 4 % faster on the
-            // 32 760 rows of the Wan-1.3B workload
-            case 3: return nchunks == 192 ? Shape{1, 3, 2, 4} : Shape{1, 3, 1, 8};
-            case 4: return {2, 2, 1, 4};
-            case 5:
-            case 6: return {2, 3, 1, 4};
-            case 7:
-            case 8: return {4, 2, 2, 1};
-            case 9:
-            case 10: return {5, 2, 2, 1};
-            case 11:
-            case 12: return {4, 3, 1, 2};
-            default: return {6, 3, 1, 1};
-        }
+        // D = 1536: three blocks per CU are 3 % faster on 126 000 rows, four are 4 % faster on the
+        // 32 760 rows of the Wan-1.3B workload
+        if (nchunks == 192) return {1, 3, 2, 4};
+        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
     const Split sp = choose_split(nchunks, dtype);
     // fp32 rows shared by several waves carry twice the bytes per wave of bf16 rows: one row per
@@ -213,22 +208,15 @@ inline Shape fwd_shape(int nchunks, int dtype) {
 
 inline Shape bwd_shape(int nchunks, int dtype) {
     if (dtype == 0) {
+        static const Shape tab[17] = {
+            {1, 1, 2, 8},
+            {1, 1, 2, 8}, {1, 2, 2, 3}, {3, 1, 1, 4}, {4, 1, 2, 2},
+            {5, 1, 2, 1}, {6, 1, 2, 1}, {4, 2, 1, 3}, {4, 2, 2, 1},
+            {5, 2, 2, 1}, {4, 3, 2, 1}, {6, 2, 1, 1}, {4, 3, 2, 1},
+            {8, 2, 1, 1}, {6, 3, 2, 1}, {6, 3, 2, 1}, {6, 3, 2, 1}};
         const int cols = (nchunks + 63) / 64;
-        switch (cols) {
-            case 1: return {1, 1, 2, 4};
-            case 2: return {1, 2, 2, 4};
-            case 3: return {3, 1, 1, nchunks == 192 ? 3 : 4};
-            case 4: return {4, 1, 2, 2};
-            case 5: return {5, 1, 2, 1};
-            case 6: return {6, 1, 2, 1};
-            case 7:
-            case 8: return {4, 2, 2, 1};
-            case 9:
-            case 10:
-            case 11:
-            case 12: return {4, 3, 2, 1};
-            default: return {6, 3, 2, 1};
-        }
+        if (nchunks == 192) return {3, 1, 1, 3};
+        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
     // fp32, rows of 1 KB and more: one row per step (a wave's four chunks of one row are as many
     // bytes as two bf16 rows) and, for the wide rows, more waves than the chunks need; timed at
@@ -252,26 +240,18 @@ inline Shape bwd_shape(int nchunks, int dtype) {
 // Backward that forms the statistics again from x.  It has one more dependent chain per step
 // (pivot, four wave sums, the merge with a division and a square root), which fewer waves per
 // row with more chunks each, or two blocks per CU, hide better than the shapes above; timed at
-// D = 512 ... 8192 on 75 600 tokens, where it then runs within 1 to 6 % of the backward that
-// reads the saved statistics (D = 2048: 14 %).
+// D = 512 ... 8192 like the tables above; it then runs 2 to 20 % behind the backward that reads
+// the saved statistics (D = 5120: 14 %).
 inline Shape rc_bwd_shape(int nchunks, int dtype) {
     if (dtype == 0) {
+        static const Shape tab[17] = {
+            {1, 1, 2, 8},
+            {1, 1, 2, 8}, {1, 2, 2, 4}, {1, 3, 2, 4}, {2, 2, 1, 4},
+            {3, 2, 2, 3}, {3, 2, 2, 2}, {4, 2, 1, 3}, {4, 2, 2, 1},
+            {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 2, 1},
+            {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}};
         const int cols = (nchunks + 63) / 64;
-        switch (cols) {
-            case 1:
-            case 2: break;
-            case 3: return {1, 3, 2, 4};
-            case 4: return {2, 2, 2, 4};
-            case 5: return {3, 2, 2, 3};
-            case 6: return {3, 2, 2, 2};
-            case 7: return {4, 2, 1, 2};
-            case 8: return {4, 2, 2, 1};
-            case 9:
-            case 10: return {4, 3, 1, 2};
-            case 11:
-            case 12: return {4, 3, 2, 1};
-            default: return {8, 2, 2, 1};
-        }
+        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
     return bwd_shape(nchunks, dtype);
 }
