@@ -70,7 +70,9 @@ typedef enum {
 /*
  * Forward (Sec. 3.3, forward kernel: statistics, normalisation and modulation in one launch,
  * statistics saved).  x, y: [B*S, D]; shift, scale: [B, D] or [B, S, D] by `mod`;
- * mean, rstd: float32 [B*S] (written).
+ * mean, rstd: float32 [B*S] (written).  mean and rstd may both be NULL (one alone is
+ * LNMOD_EINVAL): the statistics are then not stored, for callers that need only y (inference,
+ * or a backward that recomputes them, see lnmod_backward); y is the same bit for bit.
  */
 int lnmod_forward(const void* x, const void* shift, const void* scale,
                   int64_t B, int64_t S, int64_t D, float eps, void* stream,
@@ -99,7 +101,8 @@ int lnmod_backward(const void* dy, const void* x, const void* shift, const void*
  * batches of Sec. 3.2 laid end to end).  x, y: [T, D]; shift, scale: [nseg, D];
  * cu_seqlens: device int32 [nseg+1], non-decreasing, cu_seqlens[0] = 0, cu_seqlens[nseg] = T;
  * zero-length segments are allowed.  The table is read on the device only; a malformed table
- * gives unspecified values but no out-of-bounds access.  nseg plays B, T plays S.
+ * gives unspecified values but no out-of-bounds access.  nseg plays B, T plays S.  mean and rstd
+ * may both be NULL, as in lnmod_forward.
  */
 int lnmod_forward_varlen(const void* x, const void* shift, const void* scale,
                          const int32_t* cu_seqlens, int64_t nseg, int64_t T, int64_t D,

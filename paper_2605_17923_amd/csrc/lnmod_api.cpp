@@ -52,7 +52,8 @@ int forward_impl(const void* x, const void* shift, const void* scale, const int3
     if (st != LNMOD_OK) return st;
     if (T == 0) return LNMOD_OK;
     if (nseg == 0) return LNMOD_EINVAL;           // tokens that belong to no segment
-    if (!x || !shift || !scale || !y || !mean || !rstd || (varlen && !cu)) return LNMOD_EINVAL;
+    if (!x || !shift || !scale || !y || (varlen && !cu)) return LNMOD_EINVAL;
+    if ((mean == nullptr) != (rstd == nullptr)) return LNMOD_EINVAL;    // both, or neither (not stored)
     if (!aligned16(x) || !aligned16(shift) || !aligned16(scale) || !aligned16(y)) return LNMOD_EALIGN;
     const Problem p{dtype, varlen ? cu : nullptr, nseg, S, T, D, eps};
     const hipStream_t hs = static_cast<hipStream_t>(stream);

@@ -424,7 +424,7 @@ void fwd_split_kernel(const FwdArgs a) {
             for (int j = 0; j < R; ++j) {
                 const int64_t row = base + j;
                 if (row < stop) {
-                    if (kStats && wave == 0 && lane == 0) {
+                    if (kStats && wave == 0 && lane == 0 && a.mean != nullptr) {
                         a.mean[row] = mu[j];
                         a.rstd[row] = rs[j];
                     }

@@ -64,7 +64,9 @@ def bwd(dy=A, x=A, scale=A, B=2, S=4, D=64, eps=1e-6, mean=A, rstd=A, dx=A, dshi
 def test_forward_rejects_bad_arguments(lib):
     assert fwd(x=None) == lnmod.LNMOD_EINVAL
     assert fwd(shift=None) == lnmod.LNMOD_EINVAL
-    assert fwd(mean=None) == lnmod.LNMOD_EINVAL
+    assert fwd(mean=None) == lnmod.LNMOD_EINVAL                      # one statistic alone
+    assert fwd(rstd=None) == lnmod.LNMOD_EINVAL
+    assert fwd(mean=None, rstd=None, y=A + 2) == lnmod.LNMOD_EALIGN   # neither: valid so far
     assert fwd(B=-1) == lnmod.LNMOD_EINVAL
     assert fwd(S=-1) == lnmod.LNMOD_EINVAL
     assert fwd(B=1 << 20, S=1 << 20) == lnmod.LNMOD_EINVAL          # 2^40 tokens

@@ -362,6 +362,30 @@ def test_unfused_comparator_and_copy_match():
     assert torch.equal(dst, x)
 
 
+@pytest.mark.parametrize("cfg,kw", [(0, {}), (2, dict(S=1237)), (3, dict(B=2, S=301)),
+                                    (4, dict(lengths=[0, 301, 1, 0, 977, 64, 3, 0]))])
+def test_forward_without_statistics_outputs(cfg, kw):
+    # mean = rstd = NULL: nothing is stored for them and y is the same bit for bit
+    inp = synth.make_inputs(cfg, **kw)
+    w = inp.workload
+    dt, D = w.dtype, inp.D
+    st = torch.cuda.current_stream().cuda_stream
+    x, shift, scale = to_device(inp.x, dt), to_device(inp.shift, dt), to_device(inp.scale, dt)
+    code = lnmod.LNMOD_BF16 if dt == "bf16" else lnmod.LNMOD_F32
+    y1, y2 = torch.empty_like(x), torch.empty_like(x)
+    mean, rstd = torch.empty(inp.T, device="cuda"), torch.empty(inp.T, device="cuda")
+    if w.varlen:
+        cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+        assert lnmod.lnmod_forward_varlen(x, shift, scale, cu, inp.B, inp.T, D, w.eps, st, y1, mean, rstd, code) == 0
+        assert lnmod.lnmod_forward_varlen(x, shift, scale, cu, inp.B, inp.T, D, w.eps, st, y2, None, None, code) == 0
+    else:
+        mod = lnmod.LNMOD_PER_TOKEN if w.mod == synth.PER_TOKEN else lnmod.LNMOD_PER_SAMPLE
+        assert lnmod.lnmod_forward(x, shift, scale, inp.B, inp.S, D, w.eps, st, y1, mean, rstd, code, mod) == 0
+        assert lnmod.lnmod_forward(x, shift, scale, inp.B, inp.S, D, w.eps, st, y2, None, None, code, mod) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
 def test_stream_probes_move_what_they_say():
     st = torch.cuda.current_stream().cuda_stream
     n = 3 * 1024 * 1024 + 4096 + 48                    # bytes: whole pieces plus a tail that is left out
