@@ -31,6 +31,8 @@ Shape gated_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
     if (dtype == 0) {
         const int cols = (nchunks + kWave - 1) / kWave;
         if (cols == 4) sh.R = 1;                         // D = 2048: 5.97 against 5.6 TB/s
+        if (cols == 5) sh = {5, 1, 1, 1};                // D = 2560: 773 against 801 us for two rows
+        if (cols == 6) sh = {8, 1, 1, 1};                // D = 3072: 768 against 805 us for six waves
         if (cols >= 9 && cols <= 10) sh = {8, 2, 1, 1};
         if (cols >= 11 && cols <= 12) sh = {6, 2, 1, 1};
         if (cols >= 13) sh = {8, 2, 1, 1};

@@ -8,7 +8,7 @@ namespace {
 
 // Launch shape (see Shape in lnmod_launch.hpp).  The rule: the split of choose_split, two rows per
 // step, about five waves per CU.  For bf16 the widths that were timed (every shape with at most
-// 25 % padding, D = 1536 ... 8192, two machines) override it; the winners again are multiples of
+// 25 % padding, D = 1536 ... 8192, two machines; every multiple of 512 once more) override it; the winners again are multiples of
 // the four SIMDs of a CU or one block of five waves.
 int blocks_per_cu(int K) {
     if (K == 1) return 4;
@@ -21,18 +21,21 @@ Shape gated_fwd_shape(int nchunks, int dtype, bool ln) {
     const Split sp = choose_split(nchunks, dtype);
     Shape sh{sp.K, sp.VPL, 2, blocks_per_cu(sp.K)};
     if (dtype == 0 && ln) {
-        switch ((nchunks + kWave - 1) / kWave) {
+        const int cols = (nchunks + kWave - 1) / kWave;
+        switch (cols) {
             case 3: sh = {1, 3, 1, 4}; break;
             case 4: sh = {2, 2, 1, 3}; break;
             case 5:
             case 6: sh = {3, 2, 1, 2}; break;
-            case 7:
+            case 7: sh = {4, 2, 2, 1}; break;       // D = 3584: 531 against 557 us for five waves
             case 8: sh = {5, 2, 2, 1}; break;       // D = 4096: five waves, the fifth idle, beat four
-            case 9:
+            case 9: sh = {5, 2, 2, 1}; break;       // D = 4608: 517 against 546 us for four waves x 3
             case 10:
             case 11:
             case 12: sh = {4, 3, 1, 1}; break;      // D = 5120: 537 against 560 us for five waves x 2
-            default: break;
+            default:                                // D = 8192: 527 against 572 us for two rows, one block
+                if (cols >= 13) sh = {8, 2, 1, 2};
+                break;
         }
     }
     return sh;

@@ -98,7 +98,9 @@ def test_gated_bf16_d1536_three_samples():
 
 
 @pytest.mark.parametrize("D,dtype", [(1528, "bf16"), (200, "bf16"), (8, "bf16"), (8192, "bf16"), (2560, "bf16"),
-                                     (3072, "bf16"), (100, "f32"), (5120, "f32"), (8192, "f32"), (1100, "f32")])
+                                     (3072, "bf16"), (1024, "bf16"), (2048, "bf16"), (3584, "bf16"), (4096, "bf16"),
+                                     (4608, "bf16"), (5120, "bf16"), (6144, "bf16"), (7000, "bf16"),
+                                     (100, "f32"), (5120, "f32"), (8192, "f32"), (1100, "f32")])
 def test_gated_hidden_sizes(D, dtype):
     run_gated(synth.make_inputs(0, B=2, S=67, D=D, dtype=dtype), 2100 + D, label="D=%d %s" % (D, dtype))
 
