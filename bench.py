@@ -230,6 +230,8 @@ def main():
         sv_ms = _time_ms(torch, stream, bwd, iters=40, warm=5)
         rc_ms = _time_ms(torch, stream, bwd_rc, iters=40, warm=5)
         sv2_ms = _time_ms(torch, stream, bwd, iters=40, warm=5)
+        out["extras"]["torch_eager"]["fused_step_speedup"] = round(
+            out["extras"]["torch_eager"]["fwd_plus_bwd_us"] / (ms_per_step * 1e3), 2)
         out["extras"]["bwd_recompute_stats"] = {
             "recompute_us": round(rc_ms * 1e3, 1), "recompute_GBs": _gbs(T * 6 * D, rc_ms),
             "saved_stats_back_to_back_us": [round(sv_ms * 1e3, 1), round(sv2_ms * 1e3, 1)]}
@@ -419,6 +421,23 @@ def extras(lnmod, torch, x, dy, y, shift, scale, mean, rstd, T, D, st, stream, f
         x, shift, scale, 1, T, D, 1e-6, st, tmp, y, mean, rstd, lnmod.LNMOD_BF16))
     ms_f = _time_ms(torch, stream, lambda: lnmod.lnmod_forward(
         x, shift, scale, 1, T, D, 1e-6, st, y, mean, rstd, lnmod.LNMOD_BF16, lnmod.LNMOD_PER_SAMPLE))
+    # the same operator written with torch's own ops (the eager chain the paper's kernel replaces,
+    # Sec. 3.3 / Table 2): layer_norm without affine, then the modulation, in the I/O dtype
+    def eager_fwd(xx, sh, sc):
+        return torch.nn.functional.layer_norm(xx, (D,), None, None, 1e-6) * (1 + sc) + sh
+    xe = x.view(1, T, D)
+    ms_e = _time_ms(torch, stream, lambda: eager_fwd(xe, shift, scale), iters=10)
+    xg = xe.detach().clone().requires_grad_(True)
+    shg, scg = shift.detach().clone().requires_grad_(True), scale.detach().clone().requires_grad_(True)
+    dye = dy.view(1, T, D)
+
+    def eager_step():
+        xg.grad = shg.grad = scg.grad = None
+        eager_fwd(xg, shg, scg).backward(dye)
+    ms_es = _time_ms(torch, stream, eager_step, iters=10)
+    res["torch_eager"] = {"fwd_us": round(ms_e * 1e3, 1), "fwd_plus_bwd_us": round(ms_es * 1e3, 1),
+                          "fused_fwd_speedup": round(ms_e / fused_fwd_ms, 2)}
+    del xg, shg, scg
     res["unfused_fwd_us"] = round(ms_u * 1e3, 1)
     res["fused_fwd_us"] = round(ms_f * 1e3, 1)
     res["fused_vs_unfused_fwd_speedup"] = round(ms_u / ms_f, 3)
