@@ -85,7 +85,8 @@ int lnmod_forward(const void* x, const void* shift, const void* scale,
  * validated.  mean and rstd may both be NULL (one alone is LNMOD_EINVAL): the statistics are
  * then formed again from x with `eps`, for callers that keep only x between the passes
  * (Sec. 3.3: nothing but the operator's output has to be stored); the result agrees with the
- * saved-statistics result to rounding.  LNMOD_PER_SAMPLE: dshift, dscale are float32 [B, D] and `workspace` must hold
+ * saved-statistics result to rounding.
+ * LNMOD_PER_SAMPLE: dshift, dscale are float32 [B, D] and `workspace` must hold
  * lnmod_backward_workspace_bytes(B, B*S, D, mod) bytes (contents need no initialisation and
  * are garbage afterwards).  LNMOD_PER_TOKEN: dshift, dscale are [B, S, D] in the I/O dtype;
  * workspace may be NULL.
