@@ -173,3 +173,44 @@ def _sample_rows(T, cu, n=1200, seed=11):
 def test_gated_config2_full_size():
     inp = synth.make_inputs(2)
     run_gated(inp, 2008, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+
+
+def test_gated_tensors_beyond_4_gib():
+    # 450 000 tokens x 5120 bf16 = 4.6 GB per tensor (byte offsets pass 2^32); inputs drawn on the device,
+    # the oracle checks sampled rows of h, y, dx and du, most of them beyond the 4 GiB line
+    T, D = 450_000, 5120
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+
+    def big(std, mean=0.0):
+        t = torch.empty(T, D, device="cuda", dtype=torch.bfloat16)
+        for lo in range(0, T, 50_000):
+            hi = min(T, lo + 50_000)
+            t[lo:hi] = (torch.randn(hi - lo, D, generator=g, device="cuda") * std + mean).to(torch.bfloat16)
+        return t
+
+    x, u, dy, dh = big(2.0, 0.5), big(1.0), big(1.0), big(1.0)
+    small = lambda s: (s * torch.randn(1, D, generator=g, device="cuda")).to(torch.bfloat16)
+    gate, shift, scale = small(0.3), small(0.1), small(0.1)
+    v = lambda t: t.view(1, T, D)
+    h, y, mean, rstd = lnmod.gated_forward(v(x), v(u), gate, shift, scale, None, 1e-6)
+    dx, du, dgate, dsh, dsc = lnmod.gated_backward(v(dy), v(dh), h, v(u), gate, scale, mean, rstd, None, 1e-6)
+    torch.cuda.synchronize()
+    first_beyond = (1 << 32) // (D * 2) + 1
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([rng.integers(0, T, 100), rng.integers(first_beyond, T, 500),
+                                     [0, first_beyond - 1, first_beyond, T - 1]]))
+    rt = torch.from_numpy(rows).cuda()
+    host = lambda t: t.reshape(-1, D)[rt].float().cpu().numpy()
+    row = lambda t: t.float().cpu().numpy()
+    h64, y64, mean64, rstd64 = go.forward(host(x), host(u), row(gate), row(shift), row(scale), 1e-6, B=1,
+                                          S=rows.size, quant=go.QUANT_BF16)
+    assert np.array_equal(to_host64(h.reshape(T, D)[rt]), h64)
+    check_io_tensor("y", y.reshape(T, D)[rt], y64, "bf16")
+    check_stats(mean.reshape(T)[rt], rstd.reshape(T)[rt], mean64, rstd64)
+    # dx and du of a row need only that row (and the modulation rows)
+    dx64, du64, _, _, _ = go.backward(host(dy), host(dh), host(h), host(u), row(gate), row(scale), 1e-6, B=1,
+                                      S=rows.size)
+    check_io_tensor("dx", dx.reshape(T, D)[rt], dx64, "bf16")
+    check_io_tensor("du", du.reshape(T, D)[rt], du64, "bf16")
+    assert bool(torch.isfinite(dgate).all()) and bool(torch.isfinite(dsh).all()) and bool(torch.isfinite(dsc).all())

@@ -288,6 +288,118 @@ def test_config4_full_size():
     run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
 
 
+def test_tensors_beyond_4_gib():
+    # 450 000 tokens x 5120 bf16 = 4.6 GB per tensor: byte offsets pass 2^32.  Inputs are drawn on the
+    # device (seeded); the oracle checks sampled rows of y and dx, most of them beyond the 4 GiB
+    # line; dshift and dscale, which need every row, are checked against float64 torch sums taken in
+    # slices (dshift = token sum of dy is the definition itself).
+    T, D = 450_000, 5120
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242)
+    x = torch.empty(T, D, device="cuda", dtype=torch.bfloat16)
+    dy = torch.empty(T, D, device="cuda", dtype=torch.bfloat16)
+    for lo in range(0, T, 50_000):
+        hi = min(T, lo + 50_000)
+        x[lo:hi] = (torch.randn(hi - lo, D, generator=g, device="cuda") * 2 + 0.5).to(torch.bfloat16)
+        dy[lo:hi] = torch.randn(hi - lo, D, generator=g, device="cuda").to(torch.bfloat16)
+    shift = (0.1 * torch.randn(1, D, generator=g, device="cuda")).to(torch.bfloat16)
+    scale = (0.1 * torch.randn(1, D, generator=g, device="cuda")).to(torch.bfloat16)
+    y, mean, rstd = lnmod.forward(x.view(1, T, D), shift, scale, 1e-6)
+    dx, dsh, dsc = lnmod.backward(dy.view(1, T, D), x.view(1, T, D), scale, mean, rstd, 1e-6)
+    torch.cuda.synchronize()
+    first_beyond = (1 << 32) // (D * 2) + 1
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.integers(0, T, 200), rng.integers(first_beyond, T, 800),
+                                     [0, first_beyond - 1, first_beyond, T - 2, T - 1]]))
+    rt = torch.from_numpy(rows).cuda()
+    xs = x[rt].float().cpu().numpy()
+    dys = dy[rt].float().cpu().numpy()
+    sh, sc = shift.float().cpu().numpy(), scale.float().cpu().numpy()
+    y64, mean64, rstd64 = oracle.forward(xs, sh, sc, 1e-6, B=1, S=rows.size)
+    check_io_tensor("y", y.view(T, D)[rt], y64, "bf16")
+    check_stats(mean.view(T)[rt], rstd.view(T)[rt], mean64, rstd64)
+    dx64, _, _ = oracle.backward(dys, xs, sc, 1e-6, B=1, S=rows.size)      # dx of a row needs only that row
+    check_io_tensor("dx", dx.view(T, D)[rt], dx64, "bf16")
+    want_sh = torch.zeros(D, device="cuda", dtype=torch.float64)
+    want_sc = torch.zeros(D, device="cuda", dtype=torch.float64)
+    for lo in range(0, T, 50_000):
+        hi = min(T, lo + 50_000)
+        xd, dyd = x[lo:hi].double(), dy[lo:hi].double()
+        want_sh += dyd.sum(0)
+        want_sc += (dyd * torch.nn.functional.layer_norm(xd, (D,), None, None, 1e-6)).sum(0)
+    check_f32_tensor("dshift", dsh, want_sh.cpu().numpy().reshape(1, D))
+    check_f32_tensor("dscale", dsc, want_sc.cpu().numpy().reshape(1, D))
+
+
+def _big_bf16(T, D, g, std=1.0, mean=0.0):
+    t = torch.empty(T, D, device="cuda", dtype=torch.bfloat16)
+    for lo in range(0, T, 50_000):
+        hi = min(T, lo + 50_000)
+        t[lo:hi] = (torch.randn(hi - lo, D, generator=g, device="cuda") * std + mean).to(torch.bfloat16)
+    return t
+
+
+def test_per_token_tensors_beyond_4_gib():
+    # per-token modulation rows are streamed like x: sampled rows beyond the 4 GiB line, all outputs
+    T, D = 450_000, 5120
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4243)
+    x, dy = _big_bf16(T, D, g, 2.0, 0.5), _big_bf16(T, D, g)
+    shift, scale = _big_bf16(T, D, g, 0.1), _big_bf16(T, D, g, 0.1)
+    v = lambda t: t.view(1, T, D)
+    y, mean, rstd = lnmod.forward(v(x), v(shift), v(scale), 1e-6)
+    dx, dsh, dsc = lnmod.backward(v(dy), v(x), v(scale), mean, rstd, 1e-6)
+    torch.cuda.synchronize()
+    first_beyond = (1 << 32) // (D * 2) + 1
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([rng.integers(0, T, 100), rng.integers(first_beyond, T, 500),
+                                     [0, first_beyond - 1, first_beyond, T - 1]]))
+    rt = torch.from_numpy(rows).cuda()
+    host = lambda t: t.reshape(T, D)[rt].float().cpu().numpy()
+    y64, mean64, rstd64 = oracle.forward(host(x), host(shift), host(scale), 1e-6, B=1, S=rows.size,
+                                         mod=oracle.PER_TOKEN)
+    check_io_tensor("y", y.reshape(T, D)[rt], y64, "bf16")
+    check_stats(mean.reshape(T)[rt], rstd.reshape(T)[rt], mean64, rstd64)
+    dx64, dsh64, dsc64 = oracle.backward(host(dy), host(x), host(scale), 1e-6, B=1, S=rows.size,
+                                         mod=oracle.PER_TOKEN)
+    check_io_tensor("dx", dx.reshape(T, D)[rt], dx64, "bf16")
+    check_io_tensor("dshift", dsh.reshape(T, D)[rt], dsh64, "bf16")
+    check_io_tensor("dscale", dsc.reshape(T, D)[rt], dsc64, "bf16")
+
+
+def test_packed_segments_beyond_4_gib():
+    # three segments, the last two beyond the 4 GiB line; the short last one is checked in full
+    # (its dshift/dscale included), the others on sampled rows
+    D = 5120
+    lengths = [430_000, 19_000, 1_000]
+    T = sum(lengths)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4244)
+    x, dy = _big_bf16(T, D, g, 2.0, 0.5), _big_bf16(T, D, g)
+    shift = (0.1 * torch.randn(3, D, generator=g, device="cuda")).to(torch.bfloat16)
+    scale = (0.1 * torch.randn(3, D, generator=g, device="cuda")).to(torch.bfloat16)
+    cu_host = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    cu = torch.from_numpy(cu_host).cuda()
+    y, mean, rstd = lnmod.forward_varlen(x, shift, scale, cu, 1e-6)
+    dx, dsh, dsc = lnmod.backward_varlen(dy, x, scale, cu, mean, rstd, 1e-6)
+    torch.cuda.synchronize()
+    sh, sc = shift.float().cpu().numpy(), scale.float().cpu().numpy()
+    rng = np.random.default_rng(10)
+    for m in range(3):
+        lo, hi = int(cu_host[m]), int(cu_host[m + 1])
+        rows = np.arange(lo, hi) if m == 2 else np.unique(np.concatenate([rng.integers(lo, hi, 300), [lo, hi - 1]]))
+        rt = torch.from_numpy(rows).cuda()
+        xs, dys = x[rt].float().cpu().numpy(), dy[rt].float().cpu().numpy()
+        y64, mean64, rstd64 = oracle.forward(xs, sh[m:m + 1], sc[m:m + 1], 1e-6, B=1, S=rows.size)
+        check_io_tensor("y seg %d" % m, y[rt], y64, "bf16")
+        check_stats(mean[rt], rstd[rt], mean64, rstd64)
+        dx64, dsh64, dsc64 = oracle.backward(dys, xs, sc[m:m + 1], 1e-6, B=1, S=rows.size)
+        check_io_tensor("dx seg %d" % m, dx[rt], dx64, "bf16")
+        if m == 2:
+            check_f32_tensor("dshift of the last segment", dsh[2:3], dsh64)
+            check_f32_tensor("dscale of the last segment", dsc[2:3], dsc64)
+
+
 # ---- behaviour of the boundary ------------------------------------------------------------------
 def test_backward_is_bitwise_reproducible_and_uses_saved_stats():
     inp = synth.make_inputs(2, S=3001)

@@ -109,3 +109,38 @@ def test_qknorm_full_size():
     rng = np.random.default_rng(5)
     rows = np.unique(np.concatenate([rng.integers(0, 75600, 1000), [0, 1, 2, 75597, 75598, 75599]]))
     run_qk(inp, sample_rows=rows, label="full size")
+
+
+def test_qknorm_tensors_beyond_4_gib():
+    # 450 000 rows x 5120 bf16 = 4.6 GB per tensor (byte offsets pass 2^32); inputs drawn on the device,
+    # the oracle checks sampled rows of both outputs and both input gradients beyond the 4 GiB line
+    N, D = 450_000, 5120
+    g = torch.Generator(device="cuda")
+    g.manual_seed(778)
+
+    def big(std, mean=0.0):
+        t = torch.empty(N, D, device="cuda", dtype=torch.bfloat16)
+        for lo in range(0, N, 50_000):
+            hi = min(N, lo + 50_000)
+            t[lo:hi] = (torch.randn(hi - lo, D, generator=g, device="cuda") * std + mean).to(torch.bfloat16)
+        return t
+
+    q, k, dqo, dko = big(1.0), big(2.0, 0.2), big(1.0), big(1.0)
+    wq = (1 + 0.1 * torch.randn(D, generator=g, device="cuda")).to(torch.bfloat16)
+    wk = (1 + 0.1 * torch.randn(D, generator=g, device="cuda")).to(torch.bfloat16)
+    q_out, k_out, rq, rk = lnmod.qknorm_forward(q, k, wq, wk, 1e-6)
+    dq, dk, dwq, dwk = lnmod.qknorm_backward(dqo, dko, q, k, wq, wk, rq, rk, 1e-6)
+    torch.cuda.synchronize()
+    first_beyond = (1 << 32) // (D * 2) + 1
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([rng.integers(0, N, 100), rng.integers(first_beyond, N, 500),
+                                     [0, first_beyond - 1, first_beyond, N - 1]]))
+    rt = torch.from_numpy(rows).cuda()
+    host = lambda t: t[rt].float().cpu().numpy()
+    vec = lambda t: t.float().cpu().numpy()
+    for name, x_, w_, out_, dyo_, dx_ in (("q", q, wq, q_out, dqo, dq), ("k", k, wk, k_out, dko, dk)):
+        y64, _ = qo.forward_one(host(x_), vec(w_), 1e-6)
+        check_io_tensor(name + "_out", out_[rt], y64, "bf16")
+        dx64, _ = qo.backward_one(host(dyo_), host(x_), vec(w_), 1e-6)    # dx of a row needs only that row
+        check_io_tensor("d" + name, dx_[rt], dx64, "bf16")
+    assert bool(torch.isfinite(dwq).all()) and bool(torch.isfinite(dwk).all())
