@@ -498,6 +498,34 @@ def test_forward_without_statistics_outputs(cfg, kw):
     assert torch.equal(y1, y2)
 
 
+@pytest.mark.parametrize("bad", [float("inf"), float("nan")])
+def test_non_finite_input_stays_in_its_row(bad):
+    # no clamping: an inf or nan in x spoils its own row of y and dx (and the dscale sum it feeds);
+    # every other row is bit for bit what it is without it, and dshift, which does not read x, too
+    inp = synth.make_inputs(2, B=2, S=150, D=1536)
+    B, S, D = 2, 150, 1536
+    x = to_device(inp.x, "bf16").view(B, S, D)
+    dy = to_device(inp.dy, "bf16").view(B, S, D)
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    y0, m0, r0 = lnmod.forward(x, shift, scale)
+    dx0, dsh0, dsc0 = lnmod.backward(dy, x, scale, m0, r0)
+    xb = x.clone()
+    xb[1, 7, 100] = bad
+    y1, m1, r1 = lnmod.forward(xb, shift, scale)
+    dx1, dsh1, dsc1 = lnmod.backward(dy, xb, scale, m1, r1)
+    dx2, dsh2, dsc2 = lnmod.backward(dy, xb, scale, None, None)          # statistics recomputed
+    torch.cuda.synchronize()
+    keep = torch.ones(B, S, dtype=torch.bool, device="cuda")
+    keep[1, 7] = False
+    assert torch.equal(y1[keep], y0[keep]) and torch.equal(dx1[keep], dx0[keep])
+    assert not bool(torch.isfinite(y1[1, 7]).all()) and not bool(torch.isfinite(dx1[1, 7]).all())
+    assert bool(torch.isfinite(dx2[keep]).all()) and not bool(torch.isfinite(dx2[1, 7]).all())
+    assert torch.equal(dsh1, dsh0)
+    # the recomputing backward adds the rows in another order (its own launch shape)
+    assert bool(torch.isfinite(dsh2).all()) and torch.allclose(dsh2, dsh0, rtol=1e-5, atol=1e-4)
+    assert torch.equal(dsc1[0], dsc0[0]) and not bool(torch.isfinite(dsc1[1]).all())
+
+
 def test_stream_probes_move_what_they_say():
     st = torch.cuda.current_stream().cuda_stream
     n = 3 * 1024 * 1024 + 4096 + 48                    # bytes: whole pieces plus a tail that is left out
