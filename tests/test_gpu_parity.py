@@ -441,6 +441,46 @@ def test_runs_on_the_given_stream_and_overwrites_outputs():
     assert torch.equal(rstd.view_as(rstd_ref), rstd_ref)
 
 
+def test_calls_from_two_threads_on_two_streams():
+    # the library keeps no state between calls: two host threads, each with its own stream, buffers
+    # and workspace, give what the same calls give one after the other
+    import threading
+    inps = [synth.make_inputs(2, S=4001, seed=31), synth.make_inputs(4, lengths=(900, 0, 2100, 7), seed=32)]
+    dev = []
+    for inp in inps:
+        T, D = inp.T, inp.D
+        d = dict(x=to_device(inp.x, "bf16"), dy=to_device(inp.dy, "bf16"), shift=to_device(inp.shift, "bf16"),
+                 scale=to_device(inp.scale, "bf16"),
+                 cu=torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda(), nseg=inp.B, T=T, D=D)
+        dev.append(d)
+
+    def run(d, stream, out):
+        with torch.cuda.stream(stream):
+            for _ in range(20):
+                y, mean, rstd = lnmod.forward_varlen(d["x"], d["shift"], d["scale"], d["cu"], 1e-6, stream=stream)
+                dx, dsh, dsc = lnmod.backward_varlen(d["dy"], d["x"], d["scale"], d["cu"], mean, rstd, 1e-6,
+                                                     stream=stream)
+            stream.synchronize()
+        out.extend([y, dx, dsh, dsc])
+
+    serial = [[], []]
+    for d, o in zip(dev, serial):
+        run(d, torch.cuda.current_stream(), o)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]            # default priority
+    torch.cuda.synchronize()
+    threaded = [[], []]
+    threads = [threading.Thread(target=run, args=(d, s, o)) for d, s, o in zip(dev, streams, threaded)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for a, b in zip(serial, threaded):
+        assert len(b) == 4
+        for u, v in zip(a, b):
+            assert torch.equal(u, v)
+
+
 def test_empty_batch_zero_fills_reduced_gradients():
     D = 256
     dsh = torch.full((3, D), 7.0, device="cuda")
