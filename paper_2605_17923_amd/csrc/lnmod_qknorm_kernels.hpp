@@ -575,8 +575,19 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void qknorm_reduce_kernel(cons
     const int t = static_cast<int>(blockIdx.x / a.dblocks);
     float acc = 0.0f;
     if (d < a.D) {
-        for (int64_t sl = wave; sl < a.nb; sl += kReduceWaves)
-            acc += a.ws[(static_cast<int64_t>(t) * a.nb + sl) * a.D + d];
+        // eight slots requested before the first is added (a wave may have 64 of them: short rows
+        // give one slot per wave of the main kernel); the additions keep slot order
+        const float* base = a.ws + static_cast<int64_t>(t) * a.nb * a.D + d;
+        for (int64_t sl = wave; sl < a.nb; sl += 8 * kReduceWaves) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t su = sl + static_cast<int64_t>(u) * kReduceWaves;
+                v[u] = su < a.nb ? base[su * a.D] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
     }
     red[wave][lane] = acc;
     __syncthreads();
