@@ -38,6 +38,13 @@ Shape gated_fwd_shape(int nchunks, int dtype, bool ln) {
                 break;
         }
     }
+    if (dtype == 0 && !ln) {
+        // the residual-only kernel (first half of the unfused comparator) at the two model widths:
+        // D = 1536: 366 against 393 us, D = 5120: 385 against 401 us on 774 MB per tensor
+        const int cols = (nchunks + kWave - 1) / kWave;
+        if (cols == 3) sh = {3, 2, 2, 2};
+        if (cols >= 9 && cols <= 12) sh = {4, 3, 2, 1};
+    }
     return sh;
 }
 
