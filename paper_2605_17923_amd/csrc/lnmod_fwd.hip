@@ -95,7 +95,14 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    const Shape sh = MODE == kModToken ? tok_fwd_shape(a.nchunks, p.dtype) : fwd_shape(a.nchunks, p.dtype);
+    Shape sh = MODE == kModToken ? tok_fwd_shape(a.nchunks, p.dtype) : fwd_shape(a.nchunks, p.dtype);
+    if ((MODE == kLnOnly || MODE == kModOnly) && p.dtype == 0) {
+        // the two kernels of the unfused comparator get the shape that makes their chain fastest at
+        // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)
+        const int cols = (a.nchunks + kWave - 1) / kWave;
+        if (cols == 3) sh = {1, 3, 1, 8};
+        if (cols >= 9 && cols <= 10) sh = {5, 2, 1, 3};
+    }
     const bool per_segment = MODE == kModSegment || MODE == kModOnly;
     // bytes of x and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
