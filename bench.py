@@ -458,10 +458,49 @@ def extras(lnmod, torch, x, dy, y, shift, scale, mean, rstd, T, D, st, stream, f
     res["gated"] = _run_gated(lnmod, torch, stream, st, dev, T, D)
     res["qknorm"] = _run_qknorm(lnmod, torch, stream, st, dev, T, D)
     res["qknorm_per_head"] = _run_qknorm(lnmod, torch, stream, st, dev, T * (D // 128), 128)
+    # the paper's kernel table (Table 2: fused against native, forward, backward and memory, for
+    # N = 8k ... 64k) measured here at D = 5120 bf16; "native" = the torch eager chain above
+    from paper_2605_17923_amd import functional
     grid = []
     for n in range(8000, 64001, 8000):
         r = _run_workload(lnmod, torch, stream, st, dev, "N=%d" % n, 1, n, 5120, PS, seed=n)
-        grid.append({"N": n, "fwd_us": r["fwd_us"], "bwd_us": r["bwd_us"]})
+        g = torch.Generator(device=dev)
+        g.manual_seed(n)
+        xn = _randn_bf16(torch, g, (1, n, 5120), dev, 2.0, 0.5).requires_grad_(True)
+        dyn = _randn_bf16(torch, g, (1, n, 5120), dev)
+        shn = _randn_bf16(torch, g, (1, 5120), dev, 0.1).requires_grad_(True)
+        scn = _randn_bf16(torch, g, (1, 5120), dev, 0.1).requires_grad_(True)
+
+        def native_fwd():
+            return torch.nn.functional.layer_norm(xn, (5120,), None, None, 1e-6) * (1 + scn) + shn
+
+        def native_step():
+            xn.grad = shn.grad = scn.grad = None
+            native_fwd().backward(dyn)
+
+        def fused_step():
+            xn.grad = shn.grad = scn.grad = None
+            functional.ln_modulate(xn, shn, scn).backward(dyn)
+
+        with torch.no_grad():
+            nat_f = _time_ms(torch, stream, native_fwd, iters=5, warm=2)
+        nat_s = _time_ms(torch, stream, native_step, iters=5, warm=2)
+
+        def peak_mb(step):
+            xn.grad = shn.grad = scn.grad = None
+            torch.cuda.synchronize()
+            torch.cuda.reset_peak_memory_stats()
+            base = torch.cuda.memory_allocated()
+            step()
+            torch.cuda.synchronize()
+            return round((torch.cuda.max_memory_allocated() - base) / 2 ** 20)
+        mem_fused, mem_native = peak_mb(fused_step), peak_mb(native_step)
+        nat_b = max(nat_s - nat_f, 1e-6)
+        grid.append({"N": n, "fwd_us": r["fwd_us"], "bwd_us": r["bwd_us"],
+                     "native_fwd_us": round(nat_f * 1e3, 1), "native_bwd_us": round(nat_b * 1e3, 1),
+                     "fwd_speedup": round(nat_f * 1e3 / r["fwd_us"], 2), "bwd_speedup": round(nat_b * 1e3 / r["bwd_us"], 2),
+                     "mem_fused_MB": mem_fused, "mem_native_MB": mem_native})
+        del xn, dyn, shn, scn
     res["paper_table2_grid_D5120"] = grid
     return res
 
