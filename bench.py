@@ -364,7 +364,26 @@ def _run_gated(lnmod, torch, stream, st, dev, T, D, iters=20):
     uf_ms = _time_ms(torch, stream, unfused_fwd, iters=iters)
     b_ms = _time_ms(torch, stream, fused_bwd, iters=iters)
     fwd_b, bwd_b = T * (8 * D + 8), T * (12 * D + 8)
-    return {"workload": "gated residual + LN-Modulate, bf16 B=1 S=%d D=%d" % (T, D),
+    # the chain written with torch's eager ops and autograd (Sec. 4.4 compares against that kind)
+    leaves = [t.detach().clone().requires_grad_(True) for t in (x, u, gate, shift, scale)]
+
+    def eager_fwd():
+        xe, ue, ge, she, sce = leaves
+        he = xe + ge * ue
+        return he, torch.nn.functional.layer_norm(he, (D,), None, None, 1e-6) * (1 + sce) + she
+
+    def eager_step():
+        for t in leaves:
+            t.grad = None
+        he, ye = eager_fwd()
+        torch.autograd.backward([he, ye], [dh, dy])
+    with torch.no_grad():
+        ef_ms = _time_ms(torch, stream, eager_fwd, iters=5, warm=2)
+    es_ms = _time_ms(torch, stream, eager_step, iters=5, warm=2)
+    del leaves
+    eager = {"fwd_us": round(ef_ms * 1e3, 1), "fwd_plus_bwd_us": round(es_ms * 1e3, 1),
+             "fused_fwd_speedup": round(ef_ms / f_ms, 2), "fused_step_speedup": round(es_ms / (f_ms + b_ms), 2)}
+    return {"workload": "gated residual + LN-Modulate, bf16 B=1 S=%d D=%d" % (T, D), "torch_eager": eager,
             "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
             "unfused_fwd_us": round(uf_ms * 1e3, 1), "fused_vs_unfused_fwd_speedup": round(uf_ms / f_ms, 3),
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
@@ -396,7 +415,24 @@ def _run_qknorm(lnmod, torch, stream, st, dev, T, D, iters=20):
     f_ms = _time_ms(torch, stream, fwd, iters=iters)
     b_ms = _time_ms(torch, stream, bwd, iters=iters)
     fwd_b, bwd_b = T * (8 * D + 8), T * (12 * D + 8)
-    return {"workload": "Q-Norm + K-Norm, bf16 N=%d D=%d" % (T, D),
+    # the same two normalisations with torch's rms_norm and autograd
+    leaves = [t.detach().clone().requires_grad_(True) for t in (q, k, wq, wk)]
+
+    def eager_fwd():
+        qe, ke, wqe, wke = leaves
+        return (torch.nn.functional.rms_norm(qe, (D,), wqe, 1e-6), torch.nn.functional.rms_norm(ke, (D,), wke, 1e-6))
+
+    def eager_step():
+        for t in leaves:
+            t.grad = None
+        torch.autograd.backward(list(eager_fwd()), [dqo, dko])
+    with torch.no_grad():
+        ef_ms = _time_ms(torch, stream, eager_fwd, iters=5, warm=2)
+    es_ms = _time_ms(torch, stream, eager_step, iters=5, warm=2)
+    del leaves
+    eager = {"fwd_us": round(ef_ms * 1e3, 1), "fwd_plus_bwd_us": round(es_ms * 1e3, 1),
+             "fused_fwd_speedup": round(ef_ms / f_ms, 2), "fused_step_speedup": round(es_ms / (f_ms + b_ms), 2)}
+    return {"workload": "Q-Norm + K-Norm, bf16 N=%d D=%d" % (T, D), "torch_eager": eager,
             "fwd_us": round(f_ms * 1e3, 1), "fwd_GBs": _gbs(fwd_b, f_ms), "fwd_frac": round(_gbs(fwd_b, f_ms) / PEAK_HBM_GBS, 3),
             "bwd_us": round(b_ms * 1e3, 1), "bwd_GBs": _gbs(bwd_b, b_ms), "bwd_frac": round(_gbs(bwd_b, b_ms) / PEAK_HBM_GBS, 3)}
 
