@@ -18,7 +18,8 @@ SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated
            "lnmod_qknorm.hip", "lnmod_misc.hip", "lnmod_api.cpp", "lnmod_sched.cpp"]
 HEADERS = [os.path.join(CSRC, "lnmod_kernels.hpp"), os.path.join(CSRC, "lnmod_launch.hpp"),
            os.path.join(CSRC, "lnmod_gated_kernels.hpp"), os.path.join(CSRC, "lnmod_qknorm_kernels.hpp"),
-           os.path.join(INCLUDE, "lnmod.h"), os.path.join(INCLUDE, "lnmod_sched.h")]
+           os.path.join(INCLUDE, "lnmod.h"), os.path.join(INCLUDE, "lnmod_sched.h"),
+           os.path.join(INCLUDE, "lnmod_tuning.h")]
 
 # packed-fp32 instructions are switched off on purpose (some of their forms have produced wrong
 # results on these machines); the host pass warns that it does not know the feature

@@ -1,10 +1,15 @@
 // lnmod_api.cpp -- the C ABI declared in include/lnmod.h: argument validation (before any HIP
 // call, so that it can be exercised on a host without a GPU) and hand-over to the launchers.
 #include "lnmod.h"
+#include "lnmod_tuning.h"
 
 #include <cmath>
 
 #include "lnmod_launch.hpp"
+
+namespace lnmod {
+Shape g_tune_shape[kTuneFamilies] = {};
+}
 
 namespace {
 
@@ -353,6 +358,40 @@ int lnmod_stream_probe(const void* a, const void* b, void* c, size_t bytes, int 
     if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return LNMOD_EALIGN;
     const hipError_t e = lnmod::launch_stream_probe(a, b, c, bytes, mode, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
+}
+
+int lnmod_tuning_set_shape(int family, int K, int VPL, int R, int per_cu) {
+    if (family < 0 || family >= lnmod::kTuneFamilies) return LNMOD_EINVAL;
+    if (K == 0) {
+        lnmod::g_tune_shape[family] = lnmod::Shape{};
+        return LNMOD_OK;
+    }
+    if (K < 1 || K > 16 || VPL < 1 || VPL > 6 || R < 1 || R > 2 || per_cu < 1 || per_cu > 16) return LNMOD_EINVAL;
+    lnmod::g_tune_shape[family] = lnmod::Shape{K, VPL, R, per_cu};
+    return LNMOD_OK;
+}
+
+int lnmod_tuning_table_shape(int family, int64_t D, int dtype, int* out) {
+    if (family < 0 || family >= lnmod::kTuneFamilies || !out) return LNMOD_EINVAL;
+    if (dtype != LNMOD_BF16 && dtype != LNMOD_F32) return LNMOD_EINVAL;
+    const int64_t vec = dtype == LNMOD_BF16 ? 8 : 4;
+    if (D < 8 || D > lnmod::kMaxD || D % vec != 0) return LNMOD_EUNSUPPORTED;
+    const int nchunks = static_cast<int>(D / vec);
+    lnmod::Shape sh{};
+    switch (family) {
+        case lnmod::kTuneFwd: sh = lnmod::fwd_shape(nchunks, dtype); break;
+        case lnmod::kTuneBwd: sh = lnmod::bwd_shape(nchunks, dtype); break;
+        case lnmod::kTuneBwdRecompute: sh = lnmod::rc_bwd_shape(nchunks, dtype); break;
+        case lnmod::kTuneTokFwd: sh = lnmod::tok_fwd_shape(nchunks, dtype); break;
+        case lnmod::kTuneTokBwd: sh = lnmod::tok_bwd_shape(nchunks, dtype); break;
+        case lnmod::kTuneGatedFwd: sh = lnmod::gated_fwd_table_shape(nchunks, dtype); break;
+        default: sh = lnmod::gated_bwd_table_shape(nchunks, dtype); break;
+    }
+    out[0] = sh.K;
+    out[1] = sh.VPL;
+    out[2] = sh.R;
+    out[3] = sh.per_cu;
+    return LNMOD_OK;
 }
 
 }  // extern "C"

@@ -121,7 +121,8 @@ hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
 RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute) {
     const int E = dtype == 0 ? 8 : 4;
     const int nchunks = static_cast<int>(D / E);
-    const Shape sh = recompute ? rc_bwd_shape(nchunks, dtype) : bwd_shape(nchunks, dtype);
+    const Shape sh = recompute ? tuned(kTuneBwdRecompute, rc_bwd_shape(nchunks, dtype))
+                               : tuned(kTuneBwd, bwd_shape(nchunks, dtype));
     // a row moves 3 D elements (dy, x, dx), a slot 2 D floats that are written and read back
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 3.0 * elem / 5.8e6;
@@ -135,7 +136,9 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
     const bool rc = mean == nullptr;
-    const Shape sh = rc ? rc_bwd_shape(a.nchunks, p.dtype) : bwd_shape(a.nchunks, p.dtype);
+    const Shape sh = rc ? tuned(kTuneBwdRecompute, rc_bwd_shape(a.nchunks, p.dtype))
+                        : tuned(kTuneBwd, bwd_shape(a.nchunks, p.dtype));
+    if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype, rc);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
@@ -164,7 +167,8 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
                           void* dscale, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, dshift, dscale, nullptr, E);
-    const Shape sh = tok_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
+    const Shape sh = tuned(kTuneTokBwd, tok_bwd_shape(a.nchunks, p.dtype));
+    if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const RowPlan pl = plan_rows(p.T, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;

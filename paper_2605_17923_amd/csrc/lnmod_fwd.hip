@@ -95,7 +95,8 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    Shape sh = MODE == kModToken ? tok_fwd_shape(a.nchunks, p.dtype) : fwd_shape(a.nchunks, p.dtype);
+    Shape sh = MODE == kModToken ? tuned(kTuneTokFwd, tok_fwd_shape(a.nchunks, p.dtype))
+                                 : MODE == kModSegment ? tuned(kTuneFwd, fwd_shape(a.nchunks, p.dtype, p.T)) : fwd_shape(a.nchunks, p.dtype);
     if ((MODE == kLnOnly || MODE == kModOnly) && p.dtype == 0) {
         // the two kernels of the unfused comparator get the shape that makes their chain fastest at
         // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)
@@ -110,6 +111,7 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                                           sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
+    if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const bool ok = p.dtype == 0 ? dispatch<bf16_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch<f32_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
     return ok ? hipGetLastError() : hipErrorInvalidConfiguration;

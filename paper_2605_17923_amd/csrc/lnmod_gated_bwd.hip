@@ -30,12 +30,22 @@ Shape gated_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
     Shape sh{K, vpl, row_bytes <= 8192 ? 2 : 1, per_cu};
     if (dtype == 0) {
         const int cols = (nchunks + kWave - 1) / kWave;
+        if (cols == 1) sh = {1, 1, 2, 3};                // D = 512: 800 against 880 us for six blocks per CU
+        if (cols == 2) sh = {2, 1, 1, 2};                // D = 1024: 809 against 856 us
         if (cols == 4) sh.R = 1;                         // D = 2048: 5.97 against 5.6 TB/s
         if (cols == 5) sh = {5, 1, 1, 1};                // D = 2560: 773 against 801 us for two rows
         if (cols == 6) sh = {8, 1, 1, 1};                // D = 3072: 768 against 805 us for six waves
         if (cols >= 9 && cols <= 10) sh = {8, 2, 1, 1};
         if (cols >= 11 && cols <= 12) sh = {6, 2, 1, 1};
         if (cols >= 13) sh = {8, 2, 1, 1};
+    }
+    if (dtype == 1) {
+        // fp32, per 512 features: D = 512: 774 against 880 us, D = 1024: 783 against 863 us,
+        // D = 3584: 819 against 857 us
+        const int cols = (nchunks + 127) / 128;
+        if (cols == 1) sh = {1, 2, 1, 3};
+        if (cols == 2) sh = {3, 2, 1, 2};
+        if (cols == 7) sh = {8, 2, 2, 1};
     }
     return sh;
 }
@@ -87,9 +97,13 @@ bool dispatch(const GatedBwdArgs& a, Shape sh, int64_t blocks, hipStream_t st) {
 
 }  // namespace
 
+Shape gated_bwd_table_shape(int nchunks, int dtype) {
+    return gated_bwd_shape(nchunks, dtype, static_cast<int64_t>(nchunks) * 16);
+}
+
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Shape sh = gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4));
+    const Shape sh = tuned(kTuneGatedBwd, gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4)));
     // a row moves 6 D elements (dy, dh, h, u, dx, du), a slot 3 D floats written and read back
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 6.0 * elem / 5.8e6;
@@ -119,7 +133,8 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Shape sh = gated_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
+    const Shape sh = tuned(kTuneGatedBwd, gated_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4)));
+    if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const RowPlan pl = gated_bwd_plan(p.T, p.nseg, p.D, p.dtype);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;

@@ -23,19 +23,35 @@ Shape gated_fwd_shape(int nchunks, int dtype, bool ln) {
     if (dtype == 0 && ln) {
         const int cols = (nchunks + kWave - 1) / kWave;
         switch (cols) {
-            case 3: sh = {1, 3, 1, 4}; break;
+            case 2: sh = {2, 2, 1, 4}; break;       // D = 1024: 523 against 549 us for one wave
+            case 3:                                 // D = 1536: 524 against 542 us for one wave x 3
             case 4: sh = {2, 2, 1, 3}; break;
             case 5:
             case 6: sh = {3, 2, 1, 2}; break;
             case 7: sh = {4, 2, 2, 1}; break;       // D = 3584: 531 against 557 us for five waves
-            case 8: sh = {5, 2, 2, 1}; break;       // D = 4096: five waves, the fifth idle, beat four
+            case 8: sh = {4, 3, 1, 1}; break;       // D = 4096: 515 against 521 us for five waves x 2
             case 9: sh = {5, 2, 2, 1}; break;       // D = 4608: 517 against 546 us for four waves x 3
             case 10:
             case 11:
             case 12: sh = {4, 3, 1, 1}; break;      // D = 5120: 537 against 560 us for five waves x 2
+            case 13:
+            case 14: sh = {8, 2, 2, 1}; break;      // D = 6656, 7168: 530 against 583 us for one row, two blocks
+            case 15: sh = {8, 2, 1, 1}; break;      // D = 7680: 541 against 582 us for two blocks
             default:                                // D = 8192: 527 against 572 us for two rows, one block
-                if (cols >= 13) sh = {8, 2, 1, 2};
+                if (cols >= 16) sh = {8, 2, 1, 2};
                 break;
+        }
+    }
+    if (dtype == 1 && ln) {
+        // fp32, per 512 features (128 chunks): the widths where the sweep beat the rule by 2 % or more
+        switch ((nchunks + 127) / 128) {
+            case 1: sh = {1, nchunks <= 64 ? 1 : 4, 2, 4}; break;    // D = 512: 515 against 535 us
+            case 3: sh = {2, 4, 1, 2}; break;                        // D = 1536: 556 against 576 us
+            case 4: sh = {3, 4, 2, 2}; break;                        // D = 2048: 527 against 541 us
+            case 6: sh = {5, 4, 2, 1}; break;                        // D = 3072: 538 against 565 us
+            case 8: sh = {5, 4, 1, 3}; break;                        // D = 4096: 528 against 555 us
+            case 16: sh = {8, 4, 2, 2}; break;                       // D = 8192: 568 against 592 us
+            default: break;
         }
     }
     if (dtype == 0 && !ln) {
@@ -123,7 +139,8 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
+    const Shape sh = LN ? tuned(kTuneGatedFwd, gated_fwd_shape(a.nchunks, p.dtype, LN)) : gated_fwd_shape(a.nchunks, p.dtype, LN);
+    if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     // bytes of x, u, h and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (p.dtype == 0 ? 8.0 : 16.0) / 6.0e6;
     const RowPlan pl = plan_rows_clusters(p.T, p.nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R,
@@ -136,6 +153,8 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
 }
 
 }  // namespace
+
+Shape gated_fwd_table_shape(int nchunks, int dtype) { return gated_fwd_shape(nchunks, dtype, true); }
 
 hipError_t launch_gated_fwd(const Problem& p, const void* x, const void* u, const void* gate,
                             const void* shift, const void* scale, void* h, void* y, float* mean,

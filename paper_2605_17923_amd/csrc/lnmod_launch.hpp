@@ -180,7 +180,18 @@ struct Shape {
     int per_cu;
 };
 
-inline Shape fwd_shape(int nchunks, int dtype) {
+// Entry of a per-512-features table (index 1 ... 16; [0] is unused).  A row of at most 64 chunks
+// on a single wave needs one chunk per lane whatever the first entry says.
+inline Shape table_entry(const Shape (&tab)[17], int nchunks, int dtype) {
+    const int per512 = dtype == 0 ? 64 : 128;
+    const int cols = (nchunks + per512 - 1) / per512;
+    Shape sh = tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+    if (sh.K == 1 && nchunks <= 64) sh.VPL = 1;
+    return sh;
+}
+
+// T: the token count if known (0: not known); only the D = 1536 entry looks at it.
+inline Shape fwd_shape(int nchunks, int dtype, int64_t T = 0) {
     if (dtype == 0) {
         static const Shape tab[17] = {
             {1, 1, 2, 8},                                                    // (unused)
@@ -189,21 +200,20 @@ inline Shape fwd_shape(int nchunks, int dtype) {
             {4, 3, 1, 2}, {5, 2, 2, 1}, {4, 3, 1, 2}, {4, 3, 1, 2},          //      4608 ... 6144
             {6, 3, 1, 2}, {6, 3, 1, 2}, {6, 3, 1, 1}, {6, 3, 1, 1}};         //      6656 ... 8192
         const int cols = (nchunks + 63) / 64;
-        // D = 1536: three blocks per CU are 3 % faster on 126 000 rows, four are 4 % faster on the
-        // 32 760 rows of the Wan-1.3B workload
-        if (nchunks == 192) return {1, 3, 2, 4};
+        // D = 1536: four blocks per CU are 4 % faster on the 32 760 rows of the Wan-1.3B workload,
+        // the two tie on 65 520 rows, three are 3 % faster on 131 040 rows and 5 % on 252 000
+        if (nchunks == 192) return {1, 3, 2, T >= 98304 ? 3 : 4};
         return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
-    const Split sp = choose_split(nchunks, dtype);
-    // fp32 rows shared by several waves carry twice the bytes per wave of bf16 rows: one row per
-    // step and twice the blocks stream better there (266 against 287 us on 37800 x 5120)
-    const int R = sp.K > 1 ? 1 : 2;
-    int per_cu = sp.K == 1 ? 4 : sp.K == 3 ? 2 : 5 / sp.K;
-    if (per_cu < 1) per_cu = 1;
-    // the two widths where the sweep of fp32 shapes (D = 1024 ... 8192) beat the rule by 5 %
-    if (nchunks > 384 && nchunks <= 512) return {2, 4, 2, 2};
-    if (nchunks > 512 && nchunks <= 768) return {4, 4, 1, 2};
-    return {sp.K, sp.VPL, R, per_cu * (2 / R)};
+    // fp32: one row per step and two blocks per CU once several waves share a row (a wave's four
+    // chunks carry twice the bytes of a bf16 wave's two: 266 against 287 us on 37800 x 5120)
+    static const Shape tab32[17] = {
+        {1, 2, 2, 8},
+        {1, 2, 2, 8}, {1, 4, 1, 8}, {1, 6, 2, 4}, {2, 4, 2, 2},
+        {4, 4, 1, 2}, {4, 4, 1, 2}, {4, 4, 1, 2}, {4, 4, 1, 2},
+        {5, 4, 1, 2}, {5, 4, 1, 2}, {8, 4, 1, 2}, {6, 4, 1, 1},
+        {8, 4, 1, 2}, {8, 4, 1, 2}, {8, 4, 1, 2}, {8, 4, 1, 2}};
+    return table_entry(tab32, nchunks, dtype);
 }
 
 inline Shape bwd_shape(int nchunks, int dtype) {
@@ -218,23 +228,15 @@ inline Shape bwd_shape(int nchunks, int dtype) {
         if (nchunks == 192) return {3, 1, 1, 3};
         return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
-    // fp32, rows of 1 KB and more: one row per step (a wave's four chunks of one row are as many
-    // bytes as two bf16 rows) and, for the wide rows, more waves than the chunks need; timed at
-    // D = 1024 ... 8192 like the bf16 table, 3 to 11 % faster than two rows per step
-    const int kmin = (nchunks + 255) / 256;             // waves of four chunks that cover the row
-    if (nchunks > 192) {
-        switch (kmin) {
-            case 1: return {1, 4, 1, 3};
-            case 2: return {2, 4, 1, 2};
-            case 3: return {4, 4, 1, 1};
-            case 4: return {4, 4, 1, 2};
-            case 5:
-            case 6: return {6, 4, 1, 1};
-            default: return {8, 4, 1, 1};
-        }
-    }
-    const Split sp = choose_split(nchunks, dtype);      // one wave, 1 to 3 chunks per lane
-    return {sp.K, sp.VPL, 2, 4};
+    // fp32, rows of 1 KB and more: mostly one row per step (a wave's four chunks of one row are as
+    // many bytes as two bf16 rows) and, for the wide rows, more waves than the chunks need
+    static const Shape tab32[17] = {
+        {1, 2, 2, 3},
+        {1, 2, 2, 3}, {1, 4, 1, 3}, {2, 4, 1, 2}, {2, 4, 1, 2},
+        {3, 4, 2, 1}, {4, 4, 1, 1}, {5, 4, 2, 1}, {4, 4, 1, 2},
+        {6, 4, 1, 1}, {6, 4, 1, 1}, {6, 4, 1, 1}, {6, 4, 1, 1},
+        {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}};
+    return table_entry(tab32, nchunks, dtype);
 }
 
 // Backward that forms the statistics again from x.  It has one more dependent chain per step
@@ -249,55 +251,73 @@ inline Shape rc_bwd_shape(int nchunks, int dtype) {
             {1, 1, 2, 8}, {1, 2, 2, 4}, {1, 3, 2, 4}, {2, 2, 1, 4},
             {3, 2, 2, 3}, {3, 2, 2, 2}, {4, 2, 1, 3}, {4, 2, 2, 1},
             {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 2, 1},
-            {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}};
+            {8, 2, 1, 2}, {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}};
         const int cols = (nchunks + 63) / 64;
         return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
-    return bwd_shape(nchunks, dtype);
+    static const Shape tab32[17] = {
+        {1, 2, 2, 3},
+        {1, 2, 2, 3}, {1, 6, 1, 3}, {2, 4, 1, 3}, {3, 4, 1, 2},
+        {3, 4, 2, 1}, {4, 4, 1, 1}, {5, 4, 2, 1}, {4, 4, 1, 2},
+        {6, 4, 1, 1}, {6, 4, 1, 1}, {6, 4, 1, 1}, {8, 4, 1, 1},
+        {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}};
+    return table_entry(tab32, nchunks, dtype);
 }
 
-// Per-token modulation (three input streams forward; three in, three out backward).  The rule:
-// the split of choose_split, one row per step for shared rows of 4 KB and more (backward) or
-// always (forward), about ten waves per CU.  For bf16 the widths that were timed (same procedure
-// as above, D = 1536 ... 8192) override it.
+// Tuning interface (include/lnmod_tuning.h): a process-wide override of one kernel family's launch
+// shape, used by the shape sweep that produced the tables above.  An override that does not cover
+// the row makes the launch fail instead of computing on part of the row.
+enum TuneFamily { kTuneFwd = 0, kTuneBwd, kTuneBwdRecompute, kTuneTokFwd, kTuneTokBwd, kTuneGatedFwd, kTuneGatedBwd,
+                  kTuneFamilies };
+extern Shape g_tune_shape[kTuneFamilies];                 // K == 0: no override
+
+inline Shape tuned(TuneFamily f, Shape table) { return g_tune_shape[f].K > 0 ? g_tune_shape[f] : table; }
+inline bool covers(const Shape& s, int nchunks) { return s.K * s.VPL * 64 >= nchunks; }
+
+// Per-token modulation (three input streams forward; three in, three out backward).  bf16: a table
+// per 512 features like the ones above, from the same sweep over the (K, VPL) these kernels are
+// compiled for (one wave alone, or two chunks per lane on 2 to 8 waves).  Here too neighbours do
+// not share winners: D = 2560 forward takes 526 us with {3,2,2,4} and 858 us with the {3,2,1,2}
+// that is best at D = 3072.  fp32: tables of the same kind (four chunks per lane once a row is
+// shared, up to six on a single wave).
 inline Shape tok_fwd_shape(int nchunks, int dtype) {
-    const Split sp = choose_split(nchunks, dtype);
-    int per_cu = sp.K == 1 ? 8 : 10 / sp.K;
-    if (per_cu < 1) per_cu = 1;
-    Shape sh{sp.K, sp.VPL, 1, per_cu};
     if (dtype == 0) {
-        switch ((nchunks + 63) / 64) {
-            case 3: sh = {1, 3, 2, 4}; break;
-            case 4: sh = {2, 2, 1, 4}; break;
-            case 5:
-            case 6: sh = {3, 2, 1, 2}; break;
-            case 7:
-            case 8: sh = {4, 2, 2, 2}; break;
-            case 11:
-            case 12: sh = {6, 2, 2, 2}; break;
-            default: break;
-        }
+        static const Shape tab[17] = {
+            {1, 1, 2, 8},
+            {1, 1, 2, 8}, {1, 2, 2, 4}, {1, 3, 2, 4}, {2, 2, 1, 4},
+            {3, 2, 2, 4}, {3, 2, 1, 2}, {4, 2, 2, 3}, {4, 2, 1, 2},
+            {5, 2, 1, 3}, {5, 2, 1, 2}, {8, 2, 1, 2}, {6, 2, 2, 2},
+            {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 1}};
+        const int cols = (nchunks + 63) / 64;
+        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
-    return sh;
+    static const Shape tab32[17] = {
+        {1, 2, 2, 4},
+        {1, 2, 2, 4}, {1, 4, 1, 4}, {2, 4, 1, 4}, {2, 4, 2, 2},
+        {3, 4, 1, 3}, {4, 4, 2, 4}, {4, 4, 1, 2}, {4, 4, 1, 1},
+        {6, 4, 2, 2}, {5, 4, 1, 2}, {8, 4, 2, 2}, {6, 4, 1, 1},
+        {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 2}};
+    return table_entry(tab32, nchunks, dtype);
 }
 
-inline Shape tok_bwd_shape(int nchunks, int dtype, int64_t row_bytes) {
-    const Split sp = choose_split(nchunks, dtype);
-    int per_cu = sp.K == 1 ? 8 : 10 / sp.K;
-    if (per_cu < 1) per_cu = 1;
-    Shape sh{sp.K, sp.VPL, (sp.K > 1 && row_bytes >= 4096) ? 1 : 2, per_cu};
+inline Shape tok_bwd_shape(int nchunks, int dtype) {
     if (dtype == 0) {
-        switch ((nchunks + 63) / 64) {
-            case 3: sh = {1, 3, 1, 3}; break;
-            case 4: sh = {2, 2, 1, 2}; break;
-            case 5:
-            case 6: sh = {3, 2, 1, 2}; break;
-            case 7:
-            case 8: sh = {4, 2, 1, 1}; break;
-            default: break;
-        }
+        static const Shape tab[17] = {
+            {1, 1, 1, 6},
+            {1, 1, 1, 6}, {1, 2, 2, 3}, {1, 3, 1, 3}, {2, 2, 1, 2},
+            {3, 2, 1, 2}, {3, 2, 1, 2}, {4, 2, 1, 2}, {4, 2, 1, 1},
+            {6, 2, 1, 2}, {5, 2, 1, 2}, {6, 2, 2, 1}, {8, 2, 2, 1},
+            {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 1, 1}, {8, 2, 1, 1}};
+        const int cols = (nchunks + 63) / 64;
+        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
     }
-    return sh;
+    static const Shape tab32[17] = {
+        {1, 2, 2, 8},
+        {1, 2, 2, 8}, {1, 4, 1, 8}, {2, 4, 1, 2}, {2, 4, 2, 2},
+        {3, 4, 2, 1}, {3, 4, 1, 1}, {5, 4, 1, 1}, {5, 4, 1, 3},
+        {5, 4, 1, 1}, {8, 4, 2, 2}, {6, 4, 1, 1}, {6, 4, 1, 1},
+        {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 1}, {8, 4, 1, 2}};
+    return table_entry(tab32, nchunks, dtype);
 }
 
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
@@ -343,6 +363,8 @@ hipError_t launch_stream_probe(const void* a, const void* b, void* c, size_t byt
 
 // Gated residual + LayerNorm-Modulate (per-sample / per-segment gate, shift, scale).
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);
+Shape gated_fwd_table_shape(int nchunks, int dtype);             // the tables' entries, no override
+Shape gated_bwd_table_shape(int nchunks, int dtype);
 hipError_t launch_gated_fwd(const Problem& p, const void* x, const void* u, const void* gate,
                             const void* shift, const void* scale, void* h, void* y, float* mean,
                             float* rstd, hipStream_t st);

@@ -25,6 +25,11 @@ EXPORTS = ("lnmod_forward", "lnmod_backward", "lnmod_forward_varlen", "lnmod_bac
            "lnmod_copy", "lnmod_stream_probe", "lnmod_gated_forward", "lnmod_gated_backward",
            "lnmod_gated_backward_workspace_bytes", "lnmod_gate_residual", "lnmod_qknorm_forward",
            "lnmod_qknorm_backward", "lnmod_qknorm_backward_workspace_bytes")
+TUNING_EXPORTS = ("lnmod_tuning_set_shape", "lnmod_tuning_table_shape")
+
+# lnmod_tune_family of include/lnmod_tuning.h
+(LNMOD_TUNE_FORWARD, LNMOD_TUNE_BACKWARD, LNMOD_TUNE_BACKWARD_RECOMPUTE, LNMOD_TUNE_TOKEN_FORWARD,
+ LNMOD_TUNE_TOKEN_BACKWARD, LNMOD_TUNE_GATED_FORWARD, LNMOD_TUNE_GATED_BACKWARD) = range(7)
 
 _lib = None
 
@@ -83,6 +88,10 @@ def library() -> ctypes.CDLL:
                                           vp, vp, vp, vp, vp, sz, cint]
     lib.lnmod_qknorm_backward_workspace_bytes.restype = sz
     lib.lnmod_qknorm_backward_workspace_bytes.argtypes = [i64, i64]
+    lib.lnmod_tuning_set_shape.restype = cint
+    lib.lnmod_tuning_set_shape.argtypes = [cint, cint, cint, cint, cint]
+    lib.lnmod_tuning_table_shape.restype = cint
+    lib.lnmod_tuning_table_shape.argtypes = [cint, i64, cint, ctypes.POINTER(cint)]
     _lib = lib
     return lib
 
@@ -195,6 +204,17 @@ def lnmod_qknorm_backward_workspace_bytes(N, D):
 
 
 # ---- conveniences: allocate outputs with torch, raise on a non-zero status ----------------------
+def lnmod_tuning_set_shape(family, K, VPL, R, per_cu):
+    return library().lnmod_tuning_set_shape(family, K, VPL, R, per_cu)
+
+
+def lnmod_tuning_table_shape(family, D, dtype, out=None):
+    """Returns (status, (K, VPL, R, per_cu)); `out`, if given, is a ctypes int array of 4."""
+    buf = out if out is not None else (ctypes.c_int * 4)()
+    st = library().lnmod_tuning_table_shape(family, D, dtype, buf)
+    return st, tuple(buf)
+
+
 def _dtype_code(t):
     import torch
     if t.dtype == torch.bfloat16:

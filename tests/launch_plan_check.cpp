@@ -36,7 +36,7 @@ int main() {
             check_shape("bwd", dtype, D, n, bwd_shape(n, dtype));
             check_shape("rc_bwd", dtype, D, n, rc_bwd_shape(n, dtype));
             check_shape("tok_fwd", dtype, D, n, tok_fwd_shape(n, dtype));
-            check_shape("tok_bwd", dtype, D, n, tok_bwd_shape(n, dtype, static_cast<int64_t>(D) * (dtype == 0 ? 2 : 4)));
+            check_shape("tok_bwd", dtype, D, n, tok_bwd_shape(n, dtype));
         }
     }
     std::mt19937_64 rng(7);

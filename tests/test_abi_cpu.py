@@ -234,3 +234,64 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(lnmod, "LIBRARY", os.path.join(tmp_path, "nope.so"))
     with pytest.raises(RuntimeError, match="not built"):
         lnmod.lnmod_forward(A, A, A, 1, 1, 64, 1e-6, None, A, A, A, 0, 0)
+
+
+# ---- tuning interface (include/lnmod_tuning.h)
+
+TUNING_HEADER = os.path.join(ROOT, "include", "lnmod_tuning.h")
+
+
+def test_tuning_header_symbols_are_exported(lib):
+    text = re.sub(r"/\*.*?\*/", "", open(TUNING_HEADER).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(lnmod_[a-z_0-9]+)\s*\(", text)))
+    assert set(names) == set(lnmod.TUNING_EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert callable(getattr(lnmod, n)), n
+
+
+def test_tuning_set_shape_validation(lib):
+    ok = lnmod.lnmod_tuning_set_shape
+    try:
+        assert ok(-1, 1, 1, 1, 1) == 1 and ok(7, 1, 1, 1, 1) == 1
+        for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
+                    (1, 1, 1, 0), (1, 1, 1, 17)):
+            assert ok(lnmod.LNMOD_TUNE_FORWARD, *bad) == 1, bad
+        assert ok(lnmod.LNMOD_TUNE_FORWARD, 4, 3, 1, 2) == 0
+    finally:
+        for fam in range(7):
+            assert ok(fam, 0, 0, 0, 0) == 0
+
+
+def test_tuning_table_shape_matches_the_documented_entries(lib):
+    # bf16 D = 5120 (the headline width) and D = 1536, as the design notes list them
+    get = lnmod.lnmod_tuning_table_shape
+    assert get(lnmod.LNMOD_TUNE_FORWARD, 5120, 0) == (0, (5, 2, 2, 1))
+    assert get(lnmod.LNMOD_TUNE_BACKWARD, 5120, 0) == (0, (4, 3, 2, 1))
+    assert get(lnmod.LNMOD_TUNE_BACKWARD_RECOMPUTE, 5120, 0) == (0, (4, 3, 1, 2))
+    assert get(lnmod.LNMOD_TUNE_FORWARD, 1536, 0) == (0, (1, 3, 2, 4))
+    assert get(lnmod.LNMOD_TUNE_GATED_FORWARD, 5120, 0) == (0, (4, 3, 1, 1))
+    assert get(lnmod.LNMOD_TUNE_GATED_BACKWARD, 5120, 0) == (0, (8, 2, 1, 1))
+    assert get(9, 5120, 0)[0] == 1 and get(0, 5120, 2)[0] == 1
+    assert get(0, 5124, 0)[0] == 2 and get(0, 8200, 1)[0] == 2
+    # every family's entry covers its row, at every supported width and both types
+    for fam in range(7):
+        for dtype, vec in ((0, 8), (1, 4)):
+            for D in range(8, 8193, 8):
+                st, (K, VPL, R, per_cu) = get(fam, D, dtype)
+                assert st == 0
+                assert K * VPL * 64 >= D // vec and R in (1, 2) and per_cu >= 1, (fam, dtype, D)
+
+
+def test_override_that_does_not_cover_the_row_fails_before_any_launch(lib):
+    try:
+        for fam in range(7):
+            assert lnmod.lnmod_tuning_set_shape(fam, 1, 1, 1, 4) == 0      # 64 chunks: 512 bf16 features
+        assert fwd(D=520, B=1, S=8) == 5
+        assert fwd(D=520, B=1, S=8, mod=1) == 5
+        assert bwd(D=520, B=1, S=8) == 5
+        assert bwd(D=520, B=1, S=8, mean=None, rstd=None) == 5
+        assert bwd(D=520, B=1, S=8, mod=1, ws=None, ws_bytes=0) == 5
+    finally:
+        for fam in range(7):
+            lnmod.lnmod_tuning_set_shape(fam, 0, 0, 0, 0)

@@ -214,3 +214,49 @@ def test_gated_tensors_beyond_4_gib():
     check_io_tensor("dx", dx.reshape(T, D)[rt], dx64, "bf16")
     check_io_tensor("du", du.reshape(T, D)[rt], du64, "bf16")
     assert bool(torch.isfinite(dgate).all()) and bool(torch.isfinite(dsh).all()) and bool(torch.isfinite(dsc).all())
+
+
+def test_gated_every_supported_hidden_size_launches():
+    # every D the header promises must map to an instantiated kernel in both gated entry points; 3
+    # rows are checked against a float64 torch expression of the definition (not the oracle: 3000
+    # sizes, tiny rows), so a launch shape that does not cover its row shows here
+    st = torch.cuda.current_stream().cuda_stream
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    S = 3
+    for dtype, code, step, tol in ((torch.bfloat16, lnmod.LNMOD_BF16, 8, 3e-2), (torch.float32, lnmod.LNMOD_F32, 4, 2e-4)):
+        bad = []
+        for D in range(8, 8193, step):
+            big = lambda: torch.randn(S, D, generator=g, device="cuda").to(dtype)      # noqa: E731
+            small = lambda: (0.1 * torch.randn(1, D, generator=g, device="cuda")).to(dtype)   # noqa: E731
+            x, u, dy, dh = big(), big(), big(), big()
+            gate, sh, sc = small(), small(), small()
+            h, y, dx, du = (torch.empty_like(x) for _ in range(4))
+            mean, rstd = torch.empty(S, device="cuda"), torch.empty(S, device="cuda")
+            dg, dsh, dsc = (torch.empty(1, D, device="cuda") for _ in range(3))
+            ws = lnmod.gated_workspace(1, S, D, "cuda")
+            rc1 = lnmod.lnmod_gated_forward(x, u, gate, sh, sc, None, 1, S, D, 1e-6, st, h, y, mean, rstd, code)
+            rc2 = lnmod.lnmod_gated_backward(dy, dh, h, u, gate, sc, None, 1, S, D, 1e-6, st, mean, rstd, dx, du, dg,
+                                             dsh, dsc, ws, ws.numel(), code)
+            if rc1 != 0 or rc2 != 0:
+                bad.append((D, rc1, rc2))
+                continue
+            xd, ud, dyd, dhd, gd, scd, shd = (t.double() for t in (x, u, dy, dh, gate, sc, sh))
+            want_h = xd + gd * ud
+            assert float((h.double() - want_h).abs().max()) <= tol * float(want_h.abs().max() + 1), D
+            hd = h.double()                                  # the stored h is what is normalised
+            mu = hd.mean(1, keepdim=True)
+            r = 1.0 / torch.sqrt(((hd - mu) ** 2).mean(1, keepdim=True) + 1e-6)
+            xh = (hd - mu) * r
+            gg = dyd * (1 + scd)
+            want_dx = dhd + r * (gg - gg.mean(1, keepdim=True) - xh * (gg * xh).mean(1, keepdim=True))
+            assert float((y.double() - (xh * (1 + scd) + shd)).abs().max()) <= tol * 4, D
+            assert float((dx.double() - want_dx).abs().max()) <= tol * float(want_dx.abs().max() + 1), D
+            # du and dgate are formed from the unrounded dx
+            assert float((du.double() - gd * want_dx).abs().max()) <= tol * float(want_dx.abs().max() + 1), D
+            want_dg = (want_dx * ud).sum(0, keepdim=True)
+            assert float((dg.double() - want_dg).abs().max()) <= tol * float(want_dg.abs().max() + 1), D
+            assert float((dsh.double() - dyd.sum(0, keepdim=True)).abs().max()) <= 1e-4, D
+            assert float((dsc.double() - (dyd * xh).sum(0, keepdim=True)).abs().max()) <= 1e-3, D
+        torch.cuda.synchronize()
+        assert not bad, "launch failed for %d sizes, first %r" % (len(bad), bad[:5])
