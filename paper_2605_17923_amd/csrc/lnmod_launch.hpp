@@ -164,8 +164,8 @@ inline Split choose_split(int nchunks, int dtype) {
 }
 
 // Launch shape of the per-sample / per-segment kernels: K waves per row, VPL chunks per lane, R
-// rows per block and step, per_cu resident blocks per CU.  For bf16 the shape comes from a table
-// indexed by the row length in units of 64 chunks (512 features).  The tables were measured, not
+// rows per block and step, per_cu resident blocks per CU.  The shape comes from a table per element
+// type, indexed by the row length in units of 512 features.  The tables were measured, not
 // derived: every instantiated (K, VPL, R, per_cu) that covers the row with at most 60 % padding
 // and 3 to 16 waves per CU was timed on one sample of about 770 MB per tensor at every multiple of
 // 512 features from 512 to 8192 (the widths of the models of Sec. 4.1, D = 1536 and 5120, three
@@ -199,11 +199,10 @@ inline Shape fwd_shape(int nchunks, int dtype, int64_t T = 0) {
             {2, 3, 1, 4}, {4, 2, 1, 3}, {4, 2, 1, 3}, {4, 2, 2, 1},          //      2560 ... 4096
             {4, 3, 1, 2}, {5, 2, 2, 1}, {4, 3, 1, 2}, {4, 3, 1, 2},          //      4608 ... 6144
             {6, 3, 1, 2}, {6, 3, 1, 2}, {6, 3, 1, 1}, {6, 3, 1, 1}};         //      6656 ... 8192
-        const int cols = (nchunks + 63) / 64;
         // D = 1536: four blocks per CU are 4 % faster on the 32 760 rows of the Wan-1.3B workload,
         // the two tie on 65 520 rows, three are 3 % faster on 131 040 rows and 5 % on 252 000
         if (nchunks == 192) return {1, 3, 2, T >= 98304 ? 3 : 4};
-        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+        return table_entry(tab, nchunks, dtype);
     }
     // fp32: one row per step and two blocks per CU once several waves share a row (a wave's four
     // chunks carry twice the bytes of a bf16 wave's two: 266 against 287 us on 37800 x 5120)
@@ -224,9 +223,8 @@ inline Shape bwd_shape(int nchunks, int dtype) {
             {5, 1, 2, 1}, {6, 1, 2, 1}, {4, 2, 1, 3}, {4, 2, 2, 1},
             {5, 2, 2, 1}, {4, 3, 2, 1}, {6, 2, 1, 1}, {4, 3, 2, 1},
             {8, 2, 1, 1}, {6, 3, 2, 1}, {6, 3, 2, 1}, {6, 3, 2, 1}};
-        const int cols = (nchunks + 63) / 64;
         if (nchunks == 192) return {3, 1, 1, 3};
-        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+        return table_entry(tab, nchunks, dtype);
     }
     // fp32, rows of 1 KB and more: mostly one row per step (a wave's four chunks of one row are as
     // many bytes as two bf16 rows) and, for the wide rows, more waves than the chunks need
@@ -252,8 +250,7 @@ inline Shape rc_bwd_shape(int nchunks, int dtype) {
             {3, 2, 2, 3}, {3, 2, 2, 2}, {4, 2, 1, 3}, {4, 2, 2, 1},
             {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 1, 2}, {4, 3, 2, 1},
             {8, 2, 1, 2}, {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 2, 1}};
-        const int cols = (nchunks + 63) / 64;
-        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+        return table_entry(tab, nchunks, dtype);
     }
     static const Shape tab32[17] = {
         {1, 2, 2, 3},
@@ -288,8 +285,7 @@ inline Shape tok_fwd_shape(int nchunks, int dtype) {
             {3, 2, 2, 4}, {3, 2, 1, 2}, {4, 2, 2, 3}, {4, 2, 1, 2},
             {5, 2, 1, 3}, {5, 2, 1, 2}, {8, 2, 1, 2}, {6, 2, 2, 2},
             {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 1}};
-        const int cols = (nchunks + 63) / 64;
-        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+        return table_entry(tab, nchunks, dtype);
     }
     static const Shape tab32[17] = {
         {1, 2, 2, 4},
@@ -308,8 +304,7 @@ inline Shape tok_bwd_shape(int nchunks, int dtype) {
             {3, 2, 1, 2}, {3, 2, 1, 2}, {4, 2, 1, 2}, {4, 2, 1, 1},
             {6, 2, 1, 2}, {5, 2, 1, 2}, {6, 2, 2, 1}, {8, 2, 2, 1},
             {8, 2, 2, 1}, {8, 2, 2, 1}, {8, 2, 1, 1}, {8, 2, 1, 1}};
-        const int cols = (nchunks + 63) / 64;
-        return tab[cols < 1 ? 1 : cols > 16 ? 16 : cols];
+        return table_entry(tab, nchunks, dtype);
     }
     static const Shape tab32[17] = {
         {1, 2, 2, 8},

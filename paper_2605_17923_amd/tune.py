@@ -39,6 +39,11 @@ def candidates(nchunks: int):
     return out
 
 
+def _ok(status, where):
+    if status != 0:
+        raise lnmod.LnmodError(status, where)
+
+
 def _time_us(call, iters, warmup):
     for _ in range(warmup):
         call()
@@ -79,7 +84,7 @@ class Case:
         # statistics for the backward families, from the forward with the table's shape
         st = lnmod.lnmod_forward(self.x, self.shift[:1], self.scale[:1], 1, T, D, 1e-6, self._st(), self.out,
                                  self.mean, self.rstd, self.code, 0)
-        assert st == 0, lnmod.lnmod_status_string(st)
+        _ok(st, "lnmod_forward")
         torch.cuda.synchronize()
         self.ws = None
         self.prepare()
@@ -125,10 +130,10 @@ def sweep(family: str, D: int, dtype: torch.dtype, tensor_bytes: float, iters: i
     fam = FAMILIES[family]
     case = Case(family, D, dtype, tensor_bytes)
     st, table = lnmod.lnmod_tuning_table_shape(fam, D, case.code)
-    assert st == 0, lnmod.lnmod_status_string(st)
+    _ok(st, "lnmod_tuning_table_shape")
     results = []
     try:
-        assert case.run() == 0
+        _ok(case.run(), family)
         for _ in range(100):                       # bring the clocks up before the first number
             case.run()
         before = _time_us(case.run, iters, warmup)
