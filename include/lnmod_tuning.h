@@ -35,7 +35,9 @@ typedef enum {
     LNMOD_TUNE_TOKEN_FORWARD = 3,       /* LNMOD_PER_TOKEN forward                                 */
     LNMOD_TUNE_TOKEN_BACKWARD = 4,      /* LNMOD_PER_TOKEN backward                                */
     LNMOD_TUNE_GATED_FORWARD = 5,       /* lnmod_gated_forward                                     */
-    LNMOD_TUNE_GATED_BACKWARD = 6       /* lnmod_gated_backward                                    */
+    LNMOD_TUNE_GATED_BACKWARD = 6,      /* lnmod_gated_backward                                    */
+    LNMOD_TUNE_QKNORM_FORWARD = 7,      /* lnmod_qknorm_forward, rows wider than one head (more    */
+    LNMOD_TUNE_QKNORM_BACKWARD = 8      /* than 32 chunks); R must be 2.  lnmod_qknorm_backward    */
 } lnmod_tune_family;
 
 /* Returns LNMOD_OK, or LNMOD_EINVAL for an unknown family or a value outside the ranges above. */

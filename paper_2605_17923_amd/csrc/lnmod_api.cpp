@@ -385,7 +385,9 @@ int lnmod_tuning_table_shape(int family, int64_t D, int dtype, int* out) {
         case lnmod::kTuneTokFwd: sh = lnmod::tok_fwd_shape(nchunks, dtype); break;
         case lnmod::kTuneTokBwd: sh = lnmod::tok_bwd_shape(nchunks, dtype); break;
         case lnmod::kTuneGatedFwd: sh = lnmod::gated_fwd_table_shape(nchunks, dtype); break;
-        default: sh = lnmod::gated_bwd_table_shape(nchunks, dtype); break;
+        case lnmod::kTuneGatedBwd: sh = lnmod::gated_bwd_table_shape(nchunks, dtype); break;
+        case lnmod::kTuneQkFwd: sh = lnmod::qknorm_table_shape(nchunks, dtype, false); break;
+        default: sh = lnmod::qknorm_table_shape(nchunks, dtype, true); break;
     }
     out[0] = sh.K;
     out[1] = sh.VPL;

@@ -265,7 +265,7 @@ inline Shape rc_bwd_shape(int nchunks, int dtype) {
 // shape, used by the shape sweep that produced the tables above.  An override that does not cover
 // the row makes the launch fail instead of computing on part of the row.
 enum TuneFamily { kTuneFwd = 0, kTuneBwd, kTuneBwdRecompute, kTuneTokFwd, kTuneTokBwd, kTuneGatedFwd, kTuneGatedBwd,
-                  kTuneFamilies };
+                  kTuneQkFwd, kTuneQkBwd, kTuneFamilies };
 extern Shape g_tune_shape[kTuneFamilies];                 // K == 0: no override
 
 inline Shape tuned(TuneFamily f, Shape table) { return g_tune_shape[f].K > 0 ? g_tune_shape[f] : table; }
@@ -374,6 +374,7 @@ hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t st);
 
 // Fused Q-Norm + K-Norm (RMS normalisation with a learned weight of two tensors, one launch).
 int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype);      // partial-sum slots per tensor
+Shape qknorm_table_shape(int nchunks, int dtype, bool backward);  // rows wider than one head; no override
 hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void* wq, const void* wk,
                              int64_t N, int64_t D, float eps, void* q_out, void* k_out,
                              float* rstd_q, float* rstd_k, hipStream_t st);

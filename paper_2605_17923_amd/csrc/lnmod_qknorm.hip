@@ -21,6 +21,43 @@ int bwd_blocks_per_cu(int K) {
     return b < 1 ? 1 : b;
 }
 
+// Launch shape of the wide-row kernels: the split of choose_split, two rows per step, and the
+// blocks per CU above (R is fixed by the instantiations).
+Shape wide_table_shape(int nchunks, int dtype, bool backward) {
+    const Split sp = choose_split(nchunks, dtype);
+    Shape sh{sp.K, sp.VPL, kRows, backward ? bwd_blocks_per_cu(sp.K) : fwd_blocks_per_cu(sp.K)};
+    if (dtype == 0) {
+        // widths where the sweep of every compiled shape (D = 512 ... 8192, 774 MB per tensor) beat
+        // the rule by 3 % or more
+        const int cols = (nchunks + kWave - 1) / kWave;
+        if (!backward) {
+            if (cols == 1) sh.per_cu = 8;                    // D = 512: 555 against 670 us
+            if (cols == 3) sh = {1, 3, kRows, 3};            // D = 1536: 516 against 560 us
+            if (cols == 8) sh = {4, 3, kRows, 1};            // D = 4096: 527 against 562 us for 4 waves x 2
+        } else {
+            if (cols == 1) sh.per_cu = 6;                    // D = 512: 776 against 810 us
+            if (cols == 2) sh = {1, 2, kRows, 3};            // D = 1024: 760 against 833 us
+            if (cols == 3) sh = {2, 2, kRows, 3};            // D = 1536: 784 against 838 us
+            if (cols == 6) sh = {3, 2, kRows, 1};            // D = 3072: 750 against 807 us
+            if (cols == 7) sh = {4, 2, kRows, 2};            // D = 3584: 827 against 850 us
+            if (cols == 8) sh = {5, 2, kRows, 2};            // D = 4096: 778 against 805 us
+        }
+    }
+    return sh;
+}
+
+// The table's shape or the tuning override; ok is false for an override these kernels are not
+// compiled for or that does not cover the row.
+Shape wide_shape(int nchunks, int dtype, bool backward, bool* ok) {
+    const Shape sh = tuned(backward ? kTuneQkBwd : kTuneQkFwd, wide_table_shape(nchunks, dtype, backward));
+    const int wide = dtype == 0 ? 2 : 4;
+    bool compiled;
+    if (sh.K == 1) compiled = sh.VPL >= 1 && (sh.VPL <= 3 || (dtype == 1 && (sh.VPL == 4 || sh.VPL == 6)));
+    else compiled = (sh.VPL == wide && (sh.K <= 6 || sh.K == 8)) || (dtype == 0 && sh.VPL == 3 && sh.K == 4);
+    *ok = compiled && sh.R == kRows && covers(sh, nchunks);
+    return sh;
+}
+
 int32_t blocks_per_tensor(int64_t N, int per_cu) {
     int64_t nb = static_cast<int64_t>(kNumCU) * per_cu / 2;
     const int64_t need = (N + kRows - 1) / kRows;
@@ -49,6 +86,12 @@ void go_bwd(const QkBwdArgs& a, hipStream_t st) {
 // calls f.template operator()<VPL, K>() for the split; VPL_WIDE as in the other launchers
 template <typename Tag, int VPL_WIDE, typename F>
 void for_split(Split sp, F&& f) {
+    if constexpr (IO<Tag>::E == 8) {             // bf16: three chunks per lane on four waves
+        if (sp.VPL == 3 && sp.K == 4) {
+            f.template operator()<3, 4>();
+            return;
+        }
+    }
     if (sp.K == 1) {
         switch (sp.VPL) {
             case 1: f.template operator()<1, 1>(); break;
@@ -112,9 +155,12 @@ int32_t qknorm_bwd_blocks(int64_t N, int64_t D, int dtype) {
         const int r = nchunks <= 16 ? short_bwd_r<1>() : short_bwd_r<2>();
         return short_blocks_per_tensor(N, 4 * r, kShortBwdBlocksPerCu) * kShortWaves;
     }
-    const Split sp = choose_split(nchunks, dtype);
-    return blocks_per_tensor(N, bwd_blocks_per_cu(sp.K));
+    bool ok;
+    const Shape sh = wide_shape(nchunks, dtype, true, &ok);
+    return blocks_per_tensor(N, sh.per_cu);
 }
+
+Shape qknorm_table_shape(int nchunks, int dtype, bool backward) { return wide_table_shape(nchunks, dtype, backward); }
 
 hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void* wq, const void* wk,
                              int64_t N, int64_t D, float eps, void* q_out, void* k_out,
@@ -143,8 +189,11 @@ hipError_t launch_qknorm_fwd(int dtype, const void* q, const void* k, const void
         }
         return hipGetLastError();
     }
-    const Split sp = choose_split(a.nchunks, dtype);
-    a.nb = blocks_per_tensor(N, fwd_blocks_per_cu(sp.K));
+    bool ok;
+    const Shape sh = wide_shape(a.nchunks, dtype, false, &ok);
+    if (!ok) return hipErrorInvalidConfiguration;
+    const Split sp{sh.K, sh.VPL};
+    a.nb = blocks_per_tensor(N, sh.per_cu);
     if (dtype == 0) for_split<bf16_io, 2>(sp, FwdGo<bf16_io>{a, st});
     else for_split<f32_io, 4>(sp, FwdGo<f32_io>{a, st});
     return hipGetLastError();
@@ -179,7 +228,10 @@ hipError_t launch_qknorm_bwd(int dtype, const void* dq_out, const void* dk_out, 
             else hipLaunchKernelGGL((qknorm_short_bwd_kernel<f32_io, 2, short_bwd_r<2>()>), grid, block, 0, st, a);
         }
     } else {
-        const Split sp = choose_split(a.nchunks, dtype);
+        bool ok;
+        const Shape sh = wide_shape(a.nchunks, dtype, true, &ok);
+        if (!ok) return hipErrorInvalidConfiguration;
+        const Split sp{sh.K, sh.VPL};
         a.nb = slots;
         if (dtype == 0) for_split<bf16_io, 2>(sp, BwdGo<bf16_io>{a, st});
         else for_split<f32_io, 4>(sp, BwdGo<f32_io>{a, st});

@@ -29,7 +29,9 @@ TUNING_EXPORTS = ("lnmod_tuning_set_shape", "lnmod_tuning_table_shape")
 
 # lnmod_tune_family of include/lnmod_tuning.h
 (LNMOD_TUNE_FORWARD, LNMOD_TUNE_BACKWARD, LNMOD_TUNE_BACKWARD_RECOMPUTE, LNMOD_TUNE_TOKEN_FORWARD,
- LNMOD_TUNE_TOKEN_BACKWARD, LNMOD_TUNE_GATED_FORWARD, LNMOD_TUNE_GATED_BACKWARD) = range(7)
+ LNMOD_TUNE_TOKEN_BACKWARD, LNMOD_TUNE_GATED_FORWARD, LNMOD_TUNE_GATED_BACKWARD,
+ LNMOD_TUNE_QKNORM_FORWARD, LNMOD_TUNE_QKNORM_BACKWARD) = range(9)
+LNMOD_TUNE_FAMILIES = 9
 
 _lib = None
 

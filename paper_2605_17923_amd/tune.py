@@ -22,7 +22,8 @@ from . import lnmod
 FAMILIES = {"forward": lnmod.LNMOD_TUNE_FORWARD, "backward": lnmod.LNMOD_TUNE_BACKWARD,
             "backward_recompute": lnmod.LNMOD_TUNE_BACKWARD_RECOMPUTE,
             "token_forward": lnmod.LNMOD_TUNE_TOKEN_FORWARD, "token_backward": lnmod.LNMOD_TUNE_TOKEN_BACKWARD,
-            "gated_forward": lnmod.LNMOD_TUNE_GATED_FORWARD, "gated_backward": lnmod.LNMOD_TUNE_GATED_BACKWARD}
+            "gated_forward": lnmod.LNMOD_TUNE_GATED_FORWARD, "gated_backward": lnmod.LNMOD_TUNE_GATED_BACKWARD,
+            "qknorm_forward": lnmod.LNMOD_TUNE_QKNORM_FORWARD, "qknorm_backward": lnmod.LNMOD_TUNE_QKNORM_BACKWARD}
 
 
 def candidates(nchunks: int):
@@ -81,6 +82,15 @@ class Case:
             self.out2 = torch.empty(T, D, device=dev, dtype=dtype)
             if "backward" in family:
                 self.dh, self.dgate = big(), torch.empty(1, D, device=dev)
+        if family.startswith("qknorm"):          # q = x, k = u; rstd of both from the forward below
+            self.u, self.out2 = big(), torch.empty(T, D, device=dev, dtype=dtype)
+            self.wq, self.wk = (torch.ones(D, device=dev, dtype=dtype) for _ in range(2))
+            self.rstd2 = torch.empty(T, device=dev)
+            self.dwq, self.dwk = torch.empty(D, device=dev), torch.empty(D, device=dev)
+            if "backward" in family:
+                self.dh = big()
+            _ok(lnmod.lnmod_qknorm_forward(self.x, self.u, self.wq, self.wk, T, D, 1e-6, self._st(), self.out,
+                                           self.out2, self.rstd, self.rstd2, self.code), "lnmod_qknorm_forward")
         # statistics for the backward families, from the forward with the table's shape
         st = lnmod.lnmod_forward(self.x, self.shift[:1], self.scale[:1], 1, T, D, 1e-6, self._st(), self.out,
                                  self.mean, self.rstd, self.code, 0)
@@ -95,6 +105,9 @@ class Case:
             self.ws = lnmod.workspace(1, self.T, self.D, "cuda")
         elif self.family == "gated_backward":
             self.ws = lnmod.gated_workspace(1, self.T, self.D, "cuda")
+        elif self.family == "qknorm_backward":
+            n = lnmod.lnmod_qknorm_backward_workspace_bytes(self.T, self.D)
+            self.ws = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
 
     @staticmethod
     def _st():
@@ -119,7 +132,14 @@ class Case:
         if f == "gated_forward":
             return lnmod.lnmod_gated_forward(self.x, self.u, self.gate, self.shift, self.scale, None, 1, T, D, 1e-6,
                                              s, self.out, self.out2, self.mean, self.rstd, c)
+        if f == "qknorm_forward":
+            return lnmod.lnmod_qknorm_forward(self.x, self.u, self.wq, self.wk, T, D, 1e-6, s, self.out, self.out2,
+                                              self.rstd, self.rstd2, c)
         ws = self.ws
+        if f == "qknorm_backward":
+            return lnmod.lnmod_qknorm_backward(self.dy, self.dh, self.x, self.u, self.wq, self.wk, T, D, 1e-6, s,
+                                               self.rstd, self.rstd2, self.out, self.out2, self.dwq, self.dwk, ws,
+                                               ws.numel(), c)
         return lnmod.lnmod_gated_backward(self.dy, self.dh, self.x, self.u, self.gate, self.scale, None, 1, T, D,
                                           1e-6, s, self.mean, self.rstd, self.out, self.out2, self.dgate,
                                           self.dshift, self.dscale, ws, ws.numel(), c)

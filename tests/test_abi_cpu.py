@@ -253,13 +253,13 @@ def test_tuning_header_symbols_are_exported(lib):
 def test_tuning_set_shape_validation(lib):
     ok = lnmod.lnmod_tuning_set_shape
     try:
-        assert ok(-1, 1, 1, 1, 1) == 1 and ok(7, 1, 1, 1, 1) == 1
+        assert ok(-1, 1, 1, 1, 1) == 1 and ok(lnmod.LNMOD_TUNE_FAMILIES, 1, 1, 1, 1) == 1
         for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
                     (1, 1, 1, 0), (1, 1, 1, 17)):
             assert ok(lnmod.LNMOD_TUNE_FORWARD, *bad) == 1, bad
         assert ok(lnmod.LNMOD_TUNE_FORWARD, 4, 3, 1, 2) == 0
     finally:
-        for fam in range(7):
+        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
             assert ok(fam, 0, 0, 0, 0) == 0
 
 
@@ -272,10 +272,10 @@ def test_tuning_table_shape_matches_the_documented_entries(lib):
     assert get(lnmod.LNMOD_TUNE_FORWARD, 1536, 0) == (0, (1, 3, 2, 4))
     assert get(lnmod.LNMOD_TUNE_GATED_FORWARD, 5120, 0) == (0, (4, 3, 1, 1))
     assert get(lnmod.LNMOD_TUNE_GATED_BACKWARD, 5120, 0) == (0, (8, 2, 1, 1))
-    assert get(9, 5120, 0)[0] == 1 and get(0, 5120, 2)[0] == 1
+    assert get(lnmod.LNMOD_TUNE_FAMILIES, 5120, 0)[0] == 1 and get(0, 5120, 2)[0] == 1
     assert get(0, 5124, 0)[0] == 2 and get(0, 8200, 1)[0] == 2
     # every family's entry covers its row, at every supported width and both types
-    for fam in range(7):
+    for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
         for dtype, vec in ((0, 8), (1, 4)):
             for D in range(8, 8193, 8):
                 st, (K, VPL, R, per_cu) = get(fam, D, dtype)
@@ -285,7 +285,7 @@ def test_tuning_table_shape_matches_the_documented_entries(lib):
 
 def test_override_that_does_not_cover_the_row_fails_before_any_launch(lib):
     try:
-        for fam in range(7):
+        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
             assert lnmod.lnmod_tuning_set_shape(fam, 1, 1, 1, 4) == 0      # 64 chunks: 512 bf16 features
         assert fwd(D=520, B=1, S=8) == 5
         assert fwd(D=520, B=1, S=8, mod=1) == 5
@@ -293,5 +293,5 @@ def test_override_that_does_not_cover_the_row_fails_before_any_launch(lib):
         assert bwd(D=520, B=1, S=8, mean=None, rstd=None) == 5
         assert bwd(D=520, B=1, S=8, mod=1, ws=None, ws_bytes=0) == 5
     finally:
-        for fam in range(7):
+        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
             lnmod.lnmod_tuning_set_shape(fam, 0, 0, 0, 0)

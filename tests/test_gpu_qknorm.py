@@ -144,3 +144,41 @@ def test_qknorm_tensors_beyond_4_gib():
         dx64, _ = qo.backward_one(host(dyo_), host(x_), vec(w_), 1e-6)    # dx of a row needs only that row
         check_io_tensor("d" + name, dx_[rt], dx64, "bf16")
     assert bool(torch.isfinite(dwq).all()) and bool(torch.isfinite(dwk).all())
+
+
+def test_qknorm_every_supported_hidden_size_launches():
+    # every D the header promises must map to an instantiated kernel (short rows, wide rows, every
+    # launch-shape override); 5 rows are checked against a float64 torch expression of the definition
+    st = torch.cuda.current_stream().cuda_stream
+    g = torch.Generator(device="cuda")
+    g.manual_seed(13)
+    N = 5
+    for dtype, code, step, tol in ((torch.bfloat16, lnmod.LNMOD_BF16, 8, 3e-2), (torch.float32, lnmod.LNMOD_F32, 4, 2e-4)):
+        bad = []
+        for D in range(8, 8193, step):
+            big = lambda: torch.randn(N, D, generator=g, device="cuda").to(dtype)      # noqa: E731
+            wgt = lambda: (1.0 + 0.1 * torch.randn(D, generator=g, device="cuda")).to(dtype)   # noqa: E731
+            q, k, dqo, dko = big(), big(), big(), big()
+            wq, wk = wgt(), wgt()
+            qo, ko, dq, dk = (torch.empty_like(q) for _ in range(4))
+            rq, rk = torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
+            dwq, dwk = torch.empty(D, device="cuda"), torch.empty(D, device="cuda")
+            nbytes = lnmod.lnmod_qknorm_backward_workspace_bytes(N, D)
+            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+            rc1 = lnmod.lnmod_qknorm_forward(q, k, wq, wk, N, D, 1e-6, st, qo, ko, rq, rk, code)
+            rc2 = lnmod.lnmod_qknorm_backward(dqo, dko, q, k, wq, wk, N, D, 1e-6, st, rq, rk, dq, dk, dwq, dwk, ws,
+                                              ws.numel(), code)
+            if rc1 != 0 or rc2 != 0:
+                bad.append((D, rc1, rc2))
+                continue
+            for x, w, dy, y, dx, dw in ((q, wq, dqo, qo, dq, dwq), (k, wk, dko, ko, dk, dwk)):
+                xd, wd, dyd = x.double(), w.double(), dy.double()
+                r = 1.0 / torch.sqrt((xd * xd).mean(1, keepdim=True) + 1e-6)
+                xh = xd * r
+                gg = dyd * wd
+                want_dx = r * (gg - xh * (gg * xh).mean(1, keepdim=True))
+                assert float((y.double() - xh * wd).abs().max()) <= tol * 4, D
+                assert float((dx.double() - want_dx).abs().max()) <= tol * float(want_dx.abs().max() + 1), D
+                assert float((dw.double() - (dyd * xh).sum(0)).abs().max()) <= 1e-3, D
+        torch.cuda.synchronize()
+        assert not bad, "launch failed for %d sizes, first %r" % (len(bad), bad[:5])

@@ -10,7 +10,7 @@ from test_gpu_parity import run_case
 
 pytestmark = pytest.mark.gpu
 
-ALL_FAMILIES = range(7)
+ALL_FAMILIES = range(lnmod.LNMOD_TUNE_FAMILIES)
 
 
 @pytest.fixture(autouse=True)
@@ -56,7 +56,8 @@ def test_uncompiled_shape_fails_and_reset_restores_the_table_launch():
 
 @pytest.mark.parametrize("family,D", [("forward", 1536), ("backward", 1536), ("backward_recompute", 2048),
                                       ("token_forward", 1024), ("token_backward", 1024),
-                                      ("gated_forward", 1536), ("gated_backward", 1536)])
+                                      ("gated_forward", 1536), ("gated_backward", 1536),
+                                      ("qknorm_forward", 5120), ("qknorm_backward", 1536)])
 def test_sweep_runs_and_contains_the_table_entry(family, D):
     table, before, after, res = tune.sweep(family, D, torch.bfloat16, 8e6, iters=2, warmup=1)
     assert before > 0 and after > 0
