@@ -61,6 +61,13 @@ constexpr int bwd_waves_per_eu(int vpl, int elems_per_chunk, int rows) {
     const int w = 512 / regs;
     return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }
+// The backward that recomputes the statistics keeps four more sums, a pivot and the merge's
+// temporaries live: with three chunks per lane it spills at three waves per SIMD, and its launch
+// shapes of that width never put more than two there.
+constexpr int bwd_seg_waves_per_eu(int vpl, int elems_per_chunk, int rows, bool recompute) {
+    const int w = bwd_waves_per_eu(vpl, elems_per_chunk, rows);
+    return recompute && vpl * elems_per_chunk >= 24 && w > 2 ? 2 : w;
+}
 #define LNMOD_OCCUPANCY(W) __attribute__((amdgpu_waves_per_eu(W)))
 
 struct bf16_io {};
@@ -510,7 +517,7 @@ struct BwdArgs {
 // and the dshift/dscale sums are taken in the second pass, where xhat is rebuilt anyway.
 template <typename Tag, int VPL, int K, int R, bool EXACT, bool TOK = false, bool PF = true, bool RC = false>
 __global__ __launch_bounds__(K* kWave)
-LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, (TOK ? 3 : 2) * (PF ? 2 * R : R) / 2))
+LNMOD_OCCUPANCY(bwd_seg_waves_per_eu(VPL, IO<Tag>::E, (TOK ? 3 : 2) * (PF ? 2 * R : R) / 2, RC))
 void bwd_seg_kernel(const BwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
