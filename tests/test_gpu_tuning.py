@@ -65,3 +65,12 @@ def test_sweep_runs_and_contains_the_table_entry(family, D):
     assert all(us > 0 for _, us in res)
     st, again = lnmod.lnmod_tuning_table_shape(tune.FAMILIES[family], D, 0)
     assert st == 0 and again == table
+
+
+def test_command_line_entry_point(capsys):
+    rc = tune.main(["--family", "backward", "--D", "1024", "--bytes", "8e6", "--iters", "2", "--warmup", "1",
+                    "--top", "3"])
+    assert rc == 0
+    out = capsys.readouterr().out
+    assert "backward D=1024 bf16: table (1, 2, 2, 3)" in out
+    assert out.count(" us") >= 4
