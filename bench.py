@@ -232,6 +232,19 @@ def main():
         sv2_ms = _time_ms(torch, stream, bwd, iters=40, warm=5)
         out["extras"]["torch_eager"]["fused_step_speedup"] = round(
             out["extras"]["torch_eager"]["fwd_plus_bwd_us"] / (ms_per_step * 1e3), 2)
+        # the same step replayed from a HIP graph of 20 (no host work and no gaps between launches)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            cs = torch.cuda.current_stream().cuda_stream
+            for _ in range(20):
+                rc = lnmod.lnmod_forward(x, shift, scale, B, S, D, 1e-6, cs, y, mean, rstd, BF16, PER_SAMPLE)
+                rc |= lnmod.lnmod_backward(dy, x, None, scale, B, S, D, 1e-6, cs, mean, rstd, dx, dshift, dscale, ws,
+                                           ws.numel(), BF16, PER_SAMPLE)
+                assert rc == 0, lnmod.lnmod_status_string(rc)
+        torch.cuda.synchronize()
+        g_ms = _time_ms(torch, torch.cuda.current_stream(), gr.replay, iters=5, warm=2) / 20
+        out["extras"]["step_in_hip_graph"] = {"ms_per_step": round(g_ms, 4), "GBs": _gbs(fwd_b + bwd_b, g_ms)}
+        del gr
         out["extras"]["bwd_recompute_stats"] = {
             "recompute_us": round(rc_ms * 1e3, 1), "recompute_GBs": _gbs(T * 6 * D, rc_ms),
             "saved_stats_back_to_back_us": [round(sv_ms * 1e3, 1), round(sv2_ms * 1e3, 1)]}
