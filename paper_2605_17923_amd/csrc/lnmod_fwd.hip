@@ -95,8 +95,9 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    Shape sh = MODE == kModToken ? tuned(kTuneTokFwd, tok_fwd_shape(a.nchunks, p.dtype))
-                                 : MODE == kModSegment ? tuned(kTuneFwd, fwd_shape(a.nchunks, p.dtype, p.T)) : fwd_shape(a.nchunks, p.dtype);
+    Shape sh = fwd_shape(a.nchunks, p.dtype);                      // the comparators' starting point
+    if (MODE == kModToken) sh = tuned(kTuneTokFwd, tok_fwd_shape(a.nchunks, p.dtype));
+    if (MODE == kModSegment) sh = tuned(kTuneFwd, fwd_shape(a.nchunks, p.dtype, p.T));
     if ((MODE == kLnOnly || MODE == kModOnly) && p.dtype == 0) {
         // the two kernels of the unfused comparator get the shape that makes their chain fastest at
         // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)

@@ -7,9 +7,9 @@ namespace lnmod {
 namespace {
 
 // Launch shape (see Shape in lnmod_launch.hpp).  The rule: the split of choose_split, two rows per
-// step, about five waves per CU.  For bf16 the widths that were timed (every shape with at most
-// 25 % padding, D = 1536 ... 8192, two machines; every multiple of 512 once more) override it; the winners again are multiples of
-// the four SIMDs of a CU or one block of five waves.
+// step, about five waves per CU.  The widths where a sweep of every compiled shape (multiples of
+// 512 features, 774 MB per tensor, both element types) beat the rule override it; the winners
+// again are multiples of the four SIMDs of a CU or one block of five waves.
 int blocks_per_cu(int K) {
     if (K == 1) return 4;
     if (K == 3) return 2;              // three waves alone leave a CU short
@@ -139,7 +139,8 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Shape sh = LN ? tuned(kTuneGatedFwd, gated_fwd_shape(a.nchunks, p.dtype, LN)) : gated_fwd_shape(a.nchunks, p.dtype, LN);
+    Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
+    if (LN) sh = tuned(kTuneGatedFwd, sh);
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     // bytes of x, u, h and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (p.dtype == 0 ? 8.0 : 16.0) / 6.0e6;
