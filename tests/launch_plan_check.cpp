@@ -33,6 +33,7 @@ int main() {
         for (int D = E; D <= kMaxD; D += E) {
             const int n = D / E;
             check_shape("fwd", dtype, D, n, fwd_shape(n, dtype));
+            check_shape("fwd, many rows", dtype, D, n, fwd_shape(n, dtype, 1000000));
             check_shape("bwd", dtype, D, n, bwd_shape(n, dtype));
             check_shape("rc_bwd", dtype, D, n, rc_bwd_shape(n, dtype));
             check_shape("tok_fwd", dtype, D, n, tok_fwd_shape(n, dtype));
