@@ -134,33 +134,6 @@ size_t lnmod_backward_workspace_bytes(int64_t B_or_nseg, int64_t total_tokens, i
 const char* lnmod_status_string(int status);
 
 /*
- * Measurement comparators, not part of the fused path.
- *
- * lnmod_unfused_forward: the decoupled chain the paper argues against (Sec. 3.3, 3.4):
- * kernel 1 writes xhat (I/O dtype) and the statistics to HBM, kernel 2 reads xhat back and
- * applies the per-sample modulation.  xhat_tmp: [B*S, D] scratch in the I/O dtype.
- *
- * lnmod_copy: plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16), the
- * practical bandwidth ceiling the kernels are compared with.
- */
-int lnmod_unfused_forward(const void* x, const void* shift, const void* scale,
-                          int64_t B, int64_t S, int64_t D, float eps, void* stream,
-                          void* xhat_tmp, void* y, float* mean, float* rstd, int dtype);
-int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream);
-
-/*
- * lnmod_stream_probe: the same access pattern with the directions taken apart, to show what
- * the memory system gives to reads, to writes and to their mixture (the fused kernels are
- * compared with these, not only with the data-sheet peak).  a, b, c: `bytes` bytes each
- * (a multiple of 16; a tail shorter than one 4 KB or 8 KB piece is left out).
- *   LNMOD_PROBE_ADD    c = a + b in 32-bit lanes: two reads and one write, the backward's mixture
- *   LNMOD_PROBE_READ   a is read (b unused, may be NULL); c needs 1 KB and is normally not written
- *   LNMOD_PROBE_WRITE  c is filled with a position-dependent pattern (a, b unused, may be NULL)
- */
-typedef enum { LNMOD_PROBE_ADD = 1, LNMOD_PROBE_READ = 2, LNMOD_PROBE_WRITE = 3 } lnmod_probe_mode;
-int lnmod_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, void* stream);
-
-/*
  * Gated residual + LayerNorm-Modulate: the "Gate + Norm" chain the paper lists among its fused
  * operators (Sec. 4.4) without defining it; defined here as a DiT block with adaptive LayerNorm
  * has it around every LayerNorm-Modulate (Sec. 3.3):
@@ -200,13 +173,6 @@ int lnmod_gated_backward(const void* dy, const void* dh, const void* h, const vo
 
 /* Bytes of device workspace lnmod_gated_backward needs (0 for invalid arguments).  Host-only. */
 size_t lnmod_gated_backward_workspace_bytes(int64_t B_or_nseg, int64_t total_tokens, int64_t D);
-
-/*
- * Measurement comparator: only h = x + gate*u (per-sample gate [B, D]), the first kernel of the
- * unfused chain "residual update, then lnmod_forward on h".
- */
-int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t B, int64_t S,
-                        int64_t D, void* stream, void* h, int dtype);
 
 /*
  * Fused Q-Norm + K-Norm: the paper lists it among its fused operators (Sec. 4.4) without defining

@@ -1,5 +1,9 @@
-"""Builds liblnmod.so (gfx950 only) in-tree with hipcc: one object per translation unit, compiled
-in parallel, then linked.  `python -m paper_2605_17923_amd.build` rebuilds from scratch."""
+"""Builds the two shared libraries (gfx950 only) in-tree with hipcc: one object per translation
+unit, compiled in parallel, then linked twice.  liblnmod.so is the operator library (include/lnmod.h,
+include/lnmod_sched.h); liblnmod_tools.so is its measurement companion (include/lnmod_tools.h): the
+same kernel objects plus the bandwidth probes, the unfused comparators and the calls that take their
+launch shape as an argument.  Both export their C entry points only.
+`python -m paper_2605_17923_amd.build` rebuilds from scratch."""
 from __future__ import annotations
 
 import os
@@ -13,13 +17,20 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIBRARY = os.path.join(HERE, "liblnmod.so")
+TOOLS_LIBRARY = os.path.join(HERE, "liblnmod_tools.so")
 
-SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated_bwd.hip",
-           "lnmod_qknorm.hip", "lnmod_misc.hip", "lnmod_api.cpp", "lnmod_sched.cpp"]
+KERNEL_SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated_bwd.hip",
+                  "lnmod_qknorm.hip"]
+LIBRARY_SOURCES = KERNEL_SOURCES + ["lnmod_api.cpp", "lnmod_sched.cpp"]
+TOOLS_SOURCES = KERNEL_SOURCES + ["lnmod_misc.hip", "lnmod_tools_api.cpp"]
+SOURCES = LIBRARY_SOURCES + [s for s in TOOLS_SOURCES if s not in LIBRARY_SOURCES]
 HEADERS = [os.path.join(CSRC, "lnmod_kernels.hpp"), os.path.join(CSRC, "lnmod_launch.hpp"),
            os.path.join(CSRC, "lnmod_gated_kernels.hpp"), os.path.join(CSRC, "lnmod_qknorm_kernels.hpp"),
+           os.path.join(CSRC, "lnmod_api_impl.hpp"),
            os.path.join(INCLUDE, "lnmod.h"), os.path.join(INCLUDE, "lnmod_sched.h"),
-           os.path.join(INCLUDE, "lnmod_tuning.h")]
+           os.path.join(INCLUDE, "lnmod_tools.h")]
+# only the C entry points leave a library; everything else (launchers, plans) stays local to it
+VERSION_SCRIPT = "{ global: lnmod_*; local: *; };\n"
 
 # packed-fp32 instructions are switched off on purpose (some of their forms have produced wrong
 # results on these machines); the host pass warns that it does not know the feature
@@ -53,20 +64,30 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
+def _link(target: str, objs, force: bool) -> None:
+    if not (force or _stale(target, objs)):
+        return
+    script = os.path.join(BUILD_DIR, "exports.map")
+    with open(script, "w") as f:
+        f.write(VERSION_SCRIPT)
+    tmp = target + ".tmp.%d" % os.getpid()
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,--version-script=" + script,
+           "-o", tmp] + list(objs)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n%s\n%s" % (res.stdout, res.stderr))
+    os.replace(tmp, target)
+
+
 def build_library(force: bool = False, verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950 and link liblnmod.so; returns its path."""
+    """Compile every HIP source for gfx950 and link both libraries; returns liblnmod.so's path."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        objs = list(pool.map(lambda s: _compile(s, force), SOURCES))
-    if force or _stale(LIBRARY, objs):
-        tmp = LIBRARY + ".tmp.%d" % os.getpid()
-        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("link failed:\n%s\n%s" % (res.stdout, res.stderr))
-        os.replace(tmp, LIBRARY)
+        objs = dict(zip(SOURCES, pool.map(lambda s: _compile(s, force), SOURCES)))
+    _link(LIBRARY, [objs[s] for s in LIBRARY_SOURCES], force)
+    _link(TOOLS_LIBRARY, [objs[s] for s in TOOLS_SOURCES], force)
     if verbose:
-        print("built", LIBRARY)
+        print("built", LIBRARY, TOOLS_LIBRARY)
     return LIBRARY
 
 

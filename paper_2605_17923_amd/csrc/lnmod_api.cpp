@@ -1,109 +1,11 @@
-// lnmod_api.cpp -- the C ABI declared in include/lnmod.h: argument validation (before any HIP
-// call, so that it can be exercised on a host without a GPU) and hand-over to the launchers.
-#include "lnmod.h"
-#include "lnmod_tuning.h"
-
-#include <cmath>
-
-#include "lnmod_launch.hpp"
-
-namespace lnmod {
-Shape g_tune_shape[kTuneFamilies] = {};
-}
+// lnmod_api.cpp -- the C ABI declared in include/lnmod.h: the operator entry points, nothing else.
+// The library keeps no mutable state: a call's result depends on its arguments alone.
+#include "lnmod_api_impl.hpp"
 
 namespace {
 
 using lnmod::Problem;
-
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-int check_shape(int64_t nseg, int64_t S_or_T, int64_t D, float eps, int dtype, int64_t total) {
-    if (nseg < 0 || nseg >= (int64_t(1) << 24) || S_or_T < 0 || D < 0) return LNMOD_EINVAL;
-    if (!(std::isfinite(eps) && eps > 0.0f)) return LNMOD_EINVAL;
-    if (dtype != LNMOD_BF16 && dtype != LNMOD_F32) return LNMOD_EINVAL;
-    if (total < 0 || total >= (int64_t(1) << 31)) return LNMOD_EINVAL;
-    const int64_t vec = dtype == LNMOD_BF16 ? 8 : 4;
-    if (D < 8 || D > lnmod::kMaxD || D % vec != 0) return LNMOD_EUNSUPPORTED;
-    return LNMOD_OK;
-}
-
-// total tokens of a fixed-length batch, or -1 on overflow
-int64_t total_tokens(int64_t B, int64_t S) {
-    if (B < 0 || S < 0) return -1;
-    if (B == 0 || S == 0) return 0;
-    if (B > (int64_t(1) << 31) / S) return -1;
-    return B * S;
-}
-
-size_t workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
-    // partial-sum slots of the plan with the most of them (neither the dtype nor whether the
-    // statistics will be recomputed is an argument of the query)
-    int64_t slots = 0;
-    for (int v = 0; v < 4; ++v) {
-        const int dtype = v & 1;
-        if (D % (dtype == 0 ? 8 : 4) != 0) continue;
-        const lnmod::RowPlan pl = lnmod::bwd_plan(T, nseg, D, dtype, (v & 2) != 0);
-        const int64_t s = lnmod::bwd_slots(pl, nseg);
-        if (s > slots) slots = s;
-    }
-    return static_cast<size_t>(slots) * 2u * static_cast<size_t>(D) * sizeof(float);
-}
-
-int forward_impl(const void* x, const void* shift, const void* scale, const int32_t* cu,
-                 bool varlen, int64_t nseg, int64_t S, int64_t T, int64_t D, float eps,
-                 void* stream, void* y, float* mean, float* rstd, int dtype, int mod) {
-    if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
-    const int st = check_shape(nseg, varlen ? T : S, D, eps, dtype, T);
-    if (st != LNMOD_OK) return st;
-    if (T == 0) return LNMOD_OK;
-    if (nseg == 0) return LNMOD_EINVAL;           // tokens that belong to no segment
-    if (!x || !shift || !scale || !y || (varlen && !cu)) return LNMOD_EINVAL;
-    if ((mean == nullptr) != (rstd == nullptr)) return LNMOD_EINVAL;    // both, or neither (not stored)
-    if (!aligned16(x) || !aligned16(shift) || !aligned16(scale) || !aligned16(y)) return LNMOD_EALIGN;
-    const Problem p{dtype, varlen ? cu : nullptr, nseg, S, T, D, eps};
-    const hipStream_t hs = static_cast<hipStream_t>(stream);
-    const hipError_t e = (mod == LNMOD_PER_TOKEN)
-                             ? lnmod::launch_fwd_tok(p, x, shift, scale, y, mean, rstd, hs)
-                             : lnmod::launch_fwd_seg(p, x, shift, scale, y, mean, rstd, hs);
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
-
-int backward_impl(const void* dy, const void* x, const void* scale, const int32_t* cu, bool varlen,
-                  int64_t nseg, int64_t S, int64_t T, int64_t D, float eps, void* stream,
-                  const float* mean, const float* rstd, void* dx, void* dshift, void* dscale,
-                  void* workspace, size_t workspace_size, int dtype, int mod) {
-    if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
-    const int st = check_shape(nseg, varlen ? T : S, D, eps, dtype, T);
-    if (st != LNMOD_OK) return st;
-    const hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (T == 0) {
-        if (mod == LNMOD_PER_SAMPLE && nseg > 0) {      // empty sums are zeros
-            if (!dshift || !dscale) return LNMOD_EINVAL;
-            if (!aligned16(dshift) || !aligned16(dscale)) return LNMOD_EALIGN;
-            hipError_t e = lnmod::launch_zero_f32(static_cast<float*>(dshift), nseg * D, hs);
-            if (e == hipSuccess) e = lnmod::launch_zero_f32(static_cast<float*>(dscale), nseg * D, hs);
-            return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-        }
-        return LNMOD_OK;
-    }
-    if (nseg == 0) return LNMOD_EINVAL;
-    if (!dy || !x || !scale || !dx || !dshift || !dscale || (varlen && !cu)) return LNMOD_EINVAL;
-    if ((mean == nullptr) != (rstd == nullptr)) return LNMOD_EINVAL;    // both, or neither (recompute)
-    if (!aligned16(dy) || !aligned16(x) || !aligned16(scale) || !aligned16(dx) ||
-        !aligned16(dshift) || !aligned16(dscale))
-        return LNMOD_EALIGN;
-    const Problem p{dtype, varlen ? cu : nullptr, nseg, S, T, D, eps};
-    hipError_t e;
-    if (mod == LNMOD_PER_TOKEN) {
-        e = lnmod::launch_bwd_tok(p, dy, x, scale, mean, rstd, dx, dshift, dscale, hs);
-    } else {
-        if (!workspace || workspace_size < workspace_bytes(nseg, T, D)) return LNMOD_EWORKSPACE;
-        if (!aligned16(workspace)) return LNMOD_EALIGN;
-        e = lnmod::launch_bwd_seg(p, dy, x, scale, mean, rstd, dx, static_cast<float*>(dshift),
-                                  static_cast<float*>(dscale), static_cast<float*>(workspace), hs);
-    }
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
+using namespace lnmod::api;
 
 size_t gated_workspace_bytes(int64_t nseg, int64_t T, int64_t D) {
     int64_t slots = 0;
@@ -198,23 +100,6 @@ const char* lnmod_status_string(int status) {
     }
 }
 
-int lnmod_unfused_forward(const void* x, const void* shift, const void* scale, int64_t B, int64_t S,
-                          int64_t D, float eps, void* stream, void* xhat_tmp, void* y, float* mean,
-                          float* rstd, int dtype) {
-    const int64_t T = total_tokens(B, S);
-    if (T < 0) return LNMOD_EINVAL;
-    const int st = check_shape(B, S, D, eps, dtype, T);
-    if (st != LNMOD_OK) return st;
-    if (T == 0) return LNMOD_OK;
-    if (!x || !shift || !scale || !xhat_tmp || !y || !mean || !rstd) return LNMOD_EINVAL;
-    if (!aligned16(x) || !aligned16(shift) || !aligned16(scale) || !aligned16(xhat_tmp) || !aligned16(y))
-        return LNMOD_EALIGN;
-    const Problem p{dtype, nullptr, B, S, T, D, eps};
-    const hipError_t e = lnmod::launch_unfused(p, x, shift, scale, xhat_tmp, y, mean, rstd,
-                                               static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
-
 int lnmod_gated_forward(const void* x, const void* u, const void* gate, const void* shift,
                         const void* scale, const int32_t* cu_seqlens, int64_t B_or_nseg,
                         int64_t S_or_T, int64_t D, float eps, void* stream, void* h, void* y,
@@ -279,20 +164,6 @@ size_t lnmod_gated_backward_workspace_bytes(int64_t B_or_nseg, int64_t total, in
     return gated_workspace_bytes(B_or_nseg, total, D);
 }
 
-int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t B, int64_t S,
-                        int64_t D, void* stream, void* h, int dtype) {
-    const int64_t T = total_tokens(B, S);
-    if (T < 0) return LNMOD_EINVAL;
-    const int st = check_shape(B, S, D, 1.0f, dtype, T);
-    if (st != LNMOD_OK) return st;
-    if (T == 0) return LNMOD_OK;
-    if (!x || !u || !gate || !h) return LNMOD_EINVAL;
-    if (!aligned16(x) || !aligned16(u) || !aligned16(gate) || !aligned16(h)) return LNMOD_EALIGN;
-    const Problem p{dtype, nullptr, B, S, T, D, 1.0f};
-    const hipError_t e = lnmod::launch_gate_residual(p, x, u, gate, h, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
-
 int lnmod_qknorm_forward(const void* q, const void* k, const void* wq, const void* wk, int64_t N,
                          int64_t D, float eps, void* stream, void* q_out, void* k_out,
                          float* rstd_q, float* rstd_k, int dtype) {
@@ -338,62 +209,6 @@ size_t lnmod_qknorm_backward_workspace_bytes(int64_t N, int64_t D) {
     if (N < 0 || N >= (int64_t(1) << 31)) return 0;
     if (D < 8 || D > lnmod::kMaxD || D % 4 != 0) return 0;
     return qknorm_workspace_bytes(N, D);
-}
-
-int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream) {
-    if (bytes == 0) return LNMOD_OK;
-    if (!src || !dst || bytes % 16 != 0) return LNMOD_EINVAL;
-    if (!aligned16(src) || !aligned16(dst)) return LNMOD_EALIGN;
-    const hipError_t e = lnmod::launch_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
-
-int lnmod_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, void* stream) {
-    if (mode != LNMOD_PROBE_ADD && mode != LNMOD_PROBE_READ && mode != LNMOD_PROBE_WRITE) return LNMOD_EINVAL;
-    if (bytes == 0) return LNMOD_OK;
-    if (bytes % 16 != 0 || !c) return LNMOD_EINVAL;
-    if (mode != LNMOD_PROBE_WRITE && !a) return LNMOD_EINVAL;
-    if (mode == LNMOD_PROBE_ADD && !b) return LNMOD_EINVAL;
-    if (mode == LNMOD_PROBE_READ && bytes < 1024) return LNMOD_EINVAL;       // c must hold 1 KB
-    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return LNMOD_EALIGN;
-    const hipError_t e = lnmod::launch_stream_probe(a, b, c, bytes, mode, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LNMOD_OK : LNMOD_ELAUNCH;
-}
-
-int lnmod_tuning_set_shape(int family, int K, int VPL, int R, int per_cu) {
-    if (family < 0 || family >= lnmod::kTuneFamilies) return LNMOD_EINVAL;
-    if (K == 0) {
-        lnmod::g_tune_shape[family] = lnmod::Shape{};
-        return LNMOD_OK;
-    }
-    if (K < 1 || K > 16 || VPL < 1 || VPL > 6 || R < 1 || R > 2 || per_cu < 1 || per_cu > 16) return LNMOD_EINVAL;
-    lnmod::g_tune_shape[family] = lnmod::Shape{K, VPL, R, per_cu};
-    return LNMOD_OK;
-}
-
-int lnmod_tuning_table_shape(int family, int64_t D, int dtype, int* out) {
-    if (family < 0 || family >= lnmod::kTuneFamilies || !out) return LNMOD_EINVAL;
-    if (dtype != LNMOD_BF16 && dtype != LNMOD_F32) return LNMOD_EINVAL;
-    const int64_t vec = dtype == LNMOD_BF16 ? 8 : 4;
-    if (D < 8 || D > lnmod::kMaxD || D % vec != 0) return LNMOD_EUNSUPPORTED;
-    const int nchunks = static_cast<int>(D / vec);
-    lnmod::Shape sh{};
-    switch (family) {
-        case lnmod::kTuneFwd: sh = lnmod::fwd_shape(nchunks, dtype); break;
-        case lnmod::kTuneBwd: sh = lnmod::bwd_shape(nchunks, dtype); break;
-        case lnmod::kTuneBwdRecompute: sh = lnmod::rc_bwd_shape(nchunks, dtype); break;
-        case lnmod::kTuneTokFwd: sh = lnmod::tok_fwd_shape(nchunks, dtype); break;
-        case lnmod::kTuneTokBwd: sh = lnmod::tok_bwd_shape(nchunks, dtype); break;
-        case lnmod::kTuneGatedFwd: sh = lnmod::gated_fwd_table_shape(nchunks, dtype); break;
-        case lnmod::kTuneGatedBwd: sh = lnmod::gated_bwd_table_shape(nchunks, dtype); break;
-        case lnmod::kTuneQkFwd: sh = lnmod::qknorm_table_shape(nchunks, dtype, false); break;
-        default: sh = lnmod::qknorm_table_shape(nchunks, dtype, true); break;
-    }
-    out[0] = sh.K;
-    out[1] = sh.VPL;
-    out[2] = sh.R;
-    out[3] = sh.per_cu;
-    return LNMOD_OK;
 }
 
 }  // extern "C"

@@ -3,6 +3,8 @@
 #include "lnmod_kernels.hpp"
 #include "lnmod_launch.hpp"
 
+#include <cstdio>
+
 namespace lnmod {
 namespace {
 
@@ -107,27 +109,56 @@ __global__ __launch_bounds__(256) void zero_f32_kernel(float* p, int64_t n) {
 
 }  // namespace
 
+// Grid of the second pass: one block per (segment, sum, feature block) triple, at most
+// kReduceMaxGrid blocks; beyond that the blocks walk the triples with a stride of the grid.
+constexpr int64_t kReduceMaxGrid = int64_t(1) << 20;
+
 hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
     const ReduceShape sh = reduce_shape(r.seg.nseg, r.nsum, r.D, clusters, r.nb);
     const int V = sh.V, W = sh.W;
     r.dblocks = static_cast<int32_t>((r.D + kWave * V - 1) / (kWave * V));
-    const dim3 grid(static_cast<unsigned>(r.seg.nseg * r.nsum * r.dblocks)), block(W * kWave);
+    r.total = r.seg.nseg * r.nsum * r.dblocks;
+    const int64_t g = r.total < kReduceMaxGrid ? r.total : kReduceMaxGrid;
+    const dim3 grid(static_cast<unsigned>(g)), block(W * kWave);
     if (V == 4) hipLaunchKernelGGL(bwd_reduce_kernel<4>, grid, block, 0, st, r);
     else if (V == 2) hipLaunchKernelGGL(bwd_reduce_kernel<2>, grid, block, 0, st, r);
     else hipLaunchKernelGGL(bwd_reduce_kernel<1>, grid, block, 0, st, r);
     return hipGetLastError();
 }
 
-RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute) {
+namespace {
+
+// Shape and row plan of a backward launch: what the launcher uses, what sizes the workspace and
+// what describe_bwd() reports.
+struct BwdLaunch {
+    Shape sh;
+    RowPlan pl;
+    int nchunks;
+};
+
+BwdLaunch plan_bwd(int64_t T, int64_t nseg, int64_t D, int dtype, bool per_token, bool recompute,
+                   const Shape* force) {
+    BwdLaunch L;
     const int E = dtype == 0 ? 8 : 4;
-    const int nchunks = static_cast<int>(D / E);
-    const Shape sh = recompute ? tuned(kTuneBwdRecompute, rc_bwd_shape(nchunks, dtype))
-                               : tuned(kTuneBwd, bwd_shape(nchunks, dtype));
+    L.nchunks = static_cast<int>(D / E);
+    if (per_token) {
+        L.sh = pick_shape(force, tok_bwd_shape(L.nchunks, dtype));
+        L.pl = plan_rows(T, static_cast<int64_t>(kNumCU) * L.sh.per_cu, L.sh.R);
+        return L;
+    }
+    L.sh = pick_shape(force, recompute ? rc_bwd_shape(L.nchunks, dtype) : bwd_shape(L.nchunks, dtype));
     // a row moves 3 D elements (dy, x, dx), a slot 2 D floats that are written and read back
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 3.0 * elem / 5.8e6;
-    return plan_rows_slots(T, nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R, stream_us,
+    L.pl = plan_rows_slots(T, nseg, static_cast<int64_t>(kNumCU) * L.sh.per_cu, L.sh.R, stream_us,
                            16.0 / (3.0 * elem));
+    return L;
+}
+
+}  // namespace
+
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute, const Shape* force) {
+    return plan_bwd(T, nseg, D, dtype, false, recompute, force).pl;
 }
 
 hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const void* scale,
@@ -136,10 +167,10 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, nullptr, nullptr, ws, E);
     const bool rc = mean == nullptr;
-    const Shape sh = rc ? tuned(kTuneBwdRecompute, rc_bwd_shape(a.nchunks, p.dtype))
-                        : tuned(kTuneBwd, bwd_shape(a.nchunks, p.dtype));
+    const BwdLaunch L = plan_bwd(p.T, p.nseg, p.D, p.dtype, false, rc, p.force);
+    const Shape sh = L.sh;
+    const RowPlan pl = L.pl;
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
-    const RowPlan pl = bwd_plan(p.T, p.nseg, p.D, p.dtype, rc);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
@@ -167,14 +198,35 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
                           void* dscale, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     BwdArgs a = make_args(p, dy, x, scale, mean, rstd, dx, dshift, dscale, nullptr, E);
-    const Shape sh = tuned(kTuneTokBwd, tok_bwd_shape(a.nchunks, p.dtype));
+    const BwdLaunch L = plan_bwd(p.T, p.nseg, p.D, p.dtype, true, mean == nullptr, p.force);
+    const Shape sh = L.sh;
+    const RowPlan pl = L.pl;
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
-    const RowPlan pl = plan_rows(p.T, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R);
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, true>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch_seg<f32_io, true>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
     return ok ? hipGetLastError() : hipErrorInvalidConfiguration;
+}
+
+// Text that names the kernel instantiations and grids a backward call with these arguments launches
+// (template arguments in the order of bwd_seg_kernel's parameter list).
+int describe_bwd(const Problem& p, bool per_token, bool recompute, char* buf, size_t n) {
+    const BwdLaunch L = plan_bwd(p.T, p.nseg, p.D, p.dtype, per_token, recompute, p.force);
+    const bool exact = L.nchunks == L.sh.K * L.sh.VPL * kWave;
+    int k = std::snprintf(buf, n, "bwd_seg_kernel<%s, %d, %d, %d, %s, %s, true, %s> grid=%lld block=%d clusters=%lld",
+                          p.dtype == 0 ? "bf16_io" : "f32_io", L.sh.VPL, L.sh.K, L.sh.R, exact ? "true" : "false",
+                          per_token ? "true" : "false", recompute ? "true" : "false",
+                          static_cast<long long>(L.pl.blocks), L.sh.K * kWave,
+                          static_cast<long long>(L.pl.clusters));
+    if (!per_token && k > 0 && static_cast<size_t>(k) < n) {
+        const ReduceShape rs = reduce_shape(p.nseg, 2, p.D, L.pl.clusters, L.pl.nb);
+        const int64_t dblocks = (p.D + kWave * rs.V - 1) / (kWave * rs.V);
+        k += std::snprintf(buf + k, n - k, " + bwd_reduce_kernel<%d> grid=%lld block=%d slots=%lld", rs.V,
+                           static_cast<long long>(p.nseg * 2 * dblocks), rs.W * kWave,
+                           static_cast<long long>(bwd_slots(L.pl, p.nseg)));
+    }
+    return k;
 }
 
 hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t st) {

@@ -3,6 +3,8 @@
 #include "lnmod_kernels.hpp"
 #include "lnmod_launch.hpp"
 
+#include <cstdio>
+
 namespace lnmod {
 namespace {
 
@@ -90,26 +92,44 @@ bool dispatch(const FwdArgs& a, int VPL, int K, int R, int64_t blocks, hipStream
     return false;                                        // no such instantiation
 }
 
+// Shape and row plan of a forward launch: what the launcher uses and what describe_fwd() reports.
+struct FwdLaunch {
+    Shape sh;
+    RowPlan pl;
+    int nchunks;
+};
+
+FwdLaunch plan_fwd(const Problem& p, int mode) {
+    FwdLaunch L;
+    const int E = p.dtype == 0 ? 8 : 4;
+    L.nchunks = static_cast<int>(p.D / E);
+    Shape sh = fwd_shape(L.nchunks, p.dtype);                      // the comparators' starting point
+    if (mode == kModToken) sh = pick_shape(p.force, tok_fwd_shape(L.nchunks, p.dtype));
+    if (mode == kModSegment) sh = pick_shape(p.force, fwd_shape(L.nchunks, p.dtype, p.T));
+    if ((mode == kLnOnly || mode == kModOnly) && p.dtype == 0) {
+        // the two kernels of the unfused comparator get the shape that makes their chain fastest at
+        // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)
+        const int cols = (L.nchunks + kWave - 1) / kWave;
+        if (cols == 3) sh = {1, 3, 1, 8};
+        if (cols >= 9 && cols <= 10) sh = {5, 2, 1, 3};
+    }
+    const bool per_segment = mode == kModSegment || mode == kModOnly;
+    // bytes of x and y at 6 TB/s
+    const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
+    L.sh = sh;
+    L.pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
+                              sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1);
+    return L;
+}
+
 template <int MODE>
 hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const void* scale, void* y,
                        float* mean, float* rstd, hipStream_t st) {
     const int E = p.dtype == 0 ? 8 : 4;
     FwdArgs a = make_args(p, x, shift, scale, y, mean, rstd, E);
-    Shape sh = fwd_shape(a.nchunks, p.dtype);                      // the comparators' starting point
-    if (MODE == kModToken) sh = tuned(kTuneTokFwd, tok_fwd_shape(a.nchunks, p.dtype));
-    if (MODE == kModSegment) sh = tuned(kTuneFwd, fwd_shape(a.nchunks, p.dtype, p.T));
-    if ((MODE == kLnOnly || MODE == kModOnly) && p.dtype == 0) {
-        // the two kernels of the unfused comparator get the shape that makes their chain fastest at
-        // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)
-        const int cols = (a.nchunks + kWave - 1) / kWave;
-        if (cols == 3) sh = {1, 3, 1, 8};
-        if (cols >= 9 && cols <= 10) sh = {5, 2, 1, 3};
-    }
-    const bool per_segment = MODE == kModSegment || MODE == kModOnly;
-    // bytes of x and y at 6 TB/s
-    const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
-    const RowPlan pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
-                                          sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1);
+    const FwdLaunch L = plan_fwd(p, MODE);
+    const Shape sh = L.sh;
+    const RowPlan pl = L.pl;
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
@@ -136,6 +156,18 @@ hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, co
     const hipError_t e = launch_mode<kLnOnly>(p, x, nullptr, nullptr, xhat, mean, rstd, st);
     if (e != hipSuccess) return e;
     return launch_mode<kModOnly>(p, xhat, shift, scale, y, nullptr, nullptr, st);
+}
+
+// Text that names the kernel instantiation and grid a forward call with these arguments launches
+// (template arguments in the order of fwd_split_kernel's parameter list).
+int describe_fwd(const Problem& p, bool per_token, char* buf, size_t n) {
+    const int mode = per_token ? kModToken : kModSegment;
+    const FwdLaunch L = plan_fwd(p, mode);
+    const bool exact = L.nchunks == L.sh.K * L.sh.VPL * kWave;
+    return std::snprintf(buf, n, "fwd_split_kernel<%s, %d, %d, %d, %s, %d, true> grid=%lld block=%d clusters=%lld",
+                         p.dtype == 0 ? "bf16_io" : "f32_io", L.sh.VPL, L.sh.K, L.sh.R, exact ? "true" : "false",
+                         mode, static_cast<long long>(L.pl.blocks), L.sh.K * kWave,
+                         static_cast<long long>(L.pl.clusters));
 }
 
 }  // namespace lnmod

@@ -103,7 +103,7 @@ Shape gated_bwd_table_shape(int nchunks, int dtype) {
 
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype) {
     const int E = dtype == 0 ? 8 : 4;
-    const Shape sh = tuned(kTuneGatedBwd, gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4)));
+    const Shape sh = gated_bwd_shape(static_cast<int>(D / E), dtype, D * (dtype == 0 ? 2 : 4));
     // a row moves 6 D elements (dy, dh, h, u, dx, du), a slot 3 D floats written and read back
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 6.0 * elem / 5.8e6;
@@ -133,7 +133,7 @@ hipError_t launch_gated_bwd(const Problem& p, const void* dy, const void* dh, co
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    const Shape sh = tuned(kTuneGatedBwd, gated_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4)));
+    const Shape sh = gated_bwd_shape(a.nchunks, p.dtype, p.D * (p.dtype == 0 ? 2 : 4));
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const RowPlan pl = gated_bwd_plan(p.T, p.nseg, p.D, p.dtype);
     a.rows_per_cluster = pl.rows_per_cluster;

@@ -139,8 +139,7 @@ hipError_t launch(const Problem& p, const void* x, const void* u, const void* ga
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
     a.inv_D = 1.0f / static_cast<float>(p.D);
-    Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
-    if (LN) sh = tuned(kTuneGatedFwd, sh);
+    const Shape sh = gated_fwd_shape(a.nchunks, p.dtype, LN);
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     // bytes of x, u, h and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (p.dtype == 0 ? 8.0 : 16.0) / 6.0e6;

@@ -61,7 +61,7 @@ constexpr int bwd_waves_per_eu(int vpl, int elems_per_chunk, int rows) {
     const int w = 512 / regs;
     return w > LNMOD_MAX_WAVES_PER_EU ? LNMOD_MAX_WAVES_PER_EU : w < 1 ? 1 : w;
 }
-// The backward that recomputes the statistics keeps four more sums, a pivot and the merge's
+// The backward that recomputes the statistics keeps four more sums, a centre and the merge's
 // temporaries live: with three chunks per lane it spills at three waves per SIMD, and its launch
 // shapes of that width never put more than two there.
 constexpr int bwd_seg_waves_per_eu(int vpl, int elems_per_chunk, int rows, bool recompute) {
@@ -508,13 +508,16 @@ struct BwdArgs {
 };
 
 // RC: mean and rstd are not read but formed again from x, for callers that keep only x between
-// the passes (Sec. 3.3: only the operator's output has to be stored).  Everything a row needs
-// comes out of one pass over the registers and one barrier: every wave takes a pivot c (the
-// mean of the first elements its lanes hold, so that x - c is small against the row's spread)
-// and sums x-c, (x-c)^2, g and g*(x-c); the K waves' numbers are moved to one common pivot c0
-// and added (S1, S2, G1, G2; lane k of every wave takes wave k's), which gives
-//   mean = c0 + S1/D,   sum (x-mean)^2 = S2 - S1^2/D,   sum g (x-mean) = G2 - (S1/D) G1,
-// and the dshift/dscale sums are taken in the second pass, where xhat is rebuilt anyway.
+// the passes (Sec. 3.3: only the operator's output has to be stored).  The variance is two-pass
+// per wave, as in the forward: every wave first takes the mean c of its own part of the row, then
+// sums x-c (the rounding residue of c), (x-c)^2, g and g*(x-c) in one pass over the registers.
+// With one barrier the K waves' numbers are moved to one common centre c0 (wave 0's mean) and
+// added (S1, S2, G1, G2; lane k of every wave takes wave k's), which gives
+//   mean = c0 + S1/D,   sum (x-mean)^2 = S2 - S1^2/D,   sum g (x-mean) = G2 - (S1/D) G1.
+// n_0 (c0 - mean)^2 <= D var, so the subtraction in the middle loses at most a factor K of fp32
+// precision whatever the row holds (a centre taken from a few sampled elements has no such
+// bound: outliers at the sampled positions would put it far from the mean).  The dshift/dscale
+// sums are taken in the second pass, where xhat is rebuilt anyway.
 template <typename Tag, int VPL, int K, int R, bool EXACT, bool TOK = false, bool PF = true, bool RC = false>
 __global__ __launch_bounds__(K* kWave)
 LNMOD_OCCUPANCY(bwd_seg_waves_per_eu(VPL, IO<Tag>::E, (TOK ? 3 : 2) * (PF ? 2 * R : R) / 2, RC))
@@ -537,21 +540,22 @@ void bwd_seg_kernel(const BwdArgs a) {
         ok[i] = EXACT || chunk[i] < a.nchunks;
     }
     // RC: lane k < K merges wave k's sums and needs the number of features wave k holds; every
-    // wave needs one over the number of its lanes that hold a first chunk
-    float lane_cnt = 0.0f, inv_first = 0.0f;
+    // wave needs one over the number of features it holds itself
+    float lane_cnt = 0.0f, inv_own = 0.0f;
     if (RC) {
         static_assert(K <= 16, "the merge runs on one DPP row");
-        int n = 0;
+        int n = 0, own = 0;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             int left = a.nchunks - (i * K + lane) * kWave;
             left = left < 0 ? 0 : left > kWave ? kWave : left;
             n += left;
+            int mine = a.nchunks - (i * K + wave) * kWave;
+            mine = mine < 0 ? 0 : mine > kWave ? kWave : mine;
+            own += mine;
         }
         lane_cnt = lane < K ? static_cast<float>(n * E) : 0.0f;
-        int first = a.nchunks - wave * kWave;
-        first = first < 1 ? 1 : first > kWave ? kWave : first;
-        inv_first = 1.0f / static_cast<float>(first);
+        inv_own = own > 0 ? 1.0f / static_cast<float>(own * E) : 0.0f;
     }
 
     const int64_t cluster = blockIdx.x / a.nb;
@@ -630,14 +634,20 @@ void bwd_seg_kernel(const BwdArgs a) {
             // which costs a few ALU operations and saves the registers the prefetch needs.
             float c1[R], c2[R];
             if constexpr (RC) {
-                // one pass: pivot, then the four sums of this wave's part of each row
+                // this wave's part of each row: its mean (the centre), then the four centred sums
                 float piv[R], s1[R], s2[R];
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     {
-                        float v0[E];
-                        io::unpack(raw[1][j][0], v0);
-                        piv[j] = wave_sum(v0[0]) * inv_first;
+                        float s = 0.0f;
+#pragma unroll
+                        for (int i = 0; i < VPL; ++i) {
+                            float v[E];
+                            io::unpack(raw[1][j][i], v);               // dead chunks hold zeros
+#pragma unroll
+                            for (int e = 0; e < E; ++e) s += v[e];
+                        }
+                        piv[j] = wave_sum(s) * inv_own;
                     }
                     float t1 = 0.0f, t2 = 0.0f, p1 = 0.0f, p2 = 0.0f;
 #pragma unroll
@@ -679,8 +689,8 @@ void bwd_seg_kernel(const BwdArgs a) {
                 }
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    // lane k < K moves wave k's sums to the first wave's pivot c0 (e = c_k - c0 is
-                    // small); adding them over the lanes gives
+                    // lane k < K moves wave k's sums to the first wave's centre c0 (e = c_k - c0);
+                    // adding them over the lanes gives
                     //   S1 = sum (x-c0), S2 = sum (x-c0)^2, G1 = sum g, G2 = sum g (x-c0)
                     float c0 = piv[j], S1 = s1[j], S2 = s2[j], G1 = c1[j], G2 = c2[j];
                     if (K > 1) {
@@ -860,6 +870,7 @@ struct ReduceArgs {
     int32_t D;
     int32_t dblocks;         // ceil(D / (64 * V))
     int32_t nsum;            // 2 or 3
+    int64_t total;           // nseg * nsum * dblocks: (segment, sum, feature block) triples
 };
 
 constexpr int kReduceWaves = 16;     // most waves a reduce block may have
@@ -867,7 +878,9 @@ constexpr int kReduceWaves = 16;     // most waves a reduce block may have
 template <int V> struct FVec { typedef float type __attribute__((ext_vector_type(V))); };
 template <> struct FVec<1> { typedef float type; };
 
-// grid.x = nseg * nsum * dblocks, decoded as (segment, which sum, block of 64 * V features)
+// Block b takes the triples b, b + gridDim.x, ... below a.total, each decoded as (segment, which
+// sum, block of 64 * V features); the grid is min(total, a bound), so that any segment count the
+// interface admits stays inside the launch limits.
 template <int V>
 __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const ReduceArgs a) {
     using vec = typename FVec<V>::type;
@@ -875,42 +888,44 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const R
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int W = blockDim.x >> 6;
-    const int64_t bid = blockIdx.x;
-    const int d = (static_cast<int>(bid % a.dblocks) * kWave + lane) * V;
-    const int which = static_cast<int>((bid / a.dblocks) % a.nsum);
-    const int64_t m = bid / (static_cast<int64_t>(a.nsum) * a.dblocks);
-    int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
-    if (n0 < 0) n0 = 0;                       // a malformed table must not lead outside ws
-    if (n1 > a.T) n1 = a.T;
-    vec acc = vec(0.0f);
-    if (n1 > n0 && d < a.D) {
-        // clusters c_lo..c_hi touch this segment; (cluster c, segment m) owns slots (c+m)*nb ..
-        const int64_t c_lo = n0 / a.rows_per_cluster, c_hi = (n1 - 1) / a.rows_per_cluster;
-        const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
-        const float* base = a.ws + static_cast<int64_t>(which) * a.D + d;
-        const int64_t pitch = static_cast<int64_t>(a.nsum) * a.D;
-        // four slots requested before the first is added; the additions keep slot order
-        for (int64_t sl = s_lo + wave; sl < s_hi; sl += 4 * W) {
-            vec v[4];
+    for (int64_t bid = blockIdx.x; bid < a.total; bid += gridDim.x) {
+        const int d = (static_cast<int>(bid % a.dblocks) * kWave + lane) * V;
+        const int which = static_cast<int>((bid / a.dblocks) % a.nsum);
+        const int64_t m = bid / (static_cast<int64_t>(a.nsum) * a.dblocks);
+        int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
+        if (n0 < 0) n0 = 0;                       // a malformed table must not lead outside ws
+        if (n1 > a.T) n1 = a.T;
+        vec acc = vec(0.0f);
+        if (n1 > n0 && d < a.D) {
+            // clusters c_lo..c_hi touch this segment; (cluster c, segment m) owns slots (c+m)*nb ..
+            const int64_t c_lo = n0 / a.rows_per_cluster, c_hi = (n1 - 1) / a.rows_per_cluster;
+            const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
+            const float* base = a.ws + static_cast<int64_t>(which) * a.D + d;
+            const int64_t pitch = static_cast<int64_t>(a.nsum) * a.D;
+            // four slots requested before the first is added; the additions keep slot order
+            for (int64_t sl = s_lo + wave; sl < s_hi; sl += 4 * W) {
+                vec v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t su = sl + static_cast<int64_t>(u) * W;
-                v[u] = su < s_hi ? *reinterpret_cast<const vec*>(base + su * pitch) : vec(0.0f);
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t su = sl + static_cast<int64_t>(u) * W;
+                    v[u] = su < s_hi ? *reinterpret_cast<const vec*>(base + su * pitch) : vec(0.0f);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc += v[u];
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc += v[u];
         }
-    }
-    if (W > 1) {
-        red[wave][lane] = acc;
-        __syncthreads();
-        if (wave == 0) {
-            acc = red[0][lane];
-            for (int w = 1; w < W; ++w) acc += red[w][lane];
+        if (W > 1) {
+            red[wave][lane] = acc;
+            __syncthreads();
+            if (wave == 0) {
+                acc = red[0][lane];
+                for (int w = 1; w < W; ++w) acc += red[w][lane];
+            }
+            __syncthreads();                      // red is written again in the next round
         }
+        if (wave == 0 && d < a.D)
+            *reinterpret_cast<vec*>(a.out[which] + m * a.D + d) = acc;
     }
-    if (wave == 0 && d < a.D)
-        *reinterpret_cast<vec*>(a.out[which] + m * a.D + d) = acc;
 }
 
 // =============================================================================================
@@ -954,57 +969,63 @@ __global__ __launch_bounds__(kCopyWaves* kWave) void copy16_kernel(const u32x4* 
     }
 }
 
-// One-directional and two-read streams in the same pattern, to split the copy figure into what
-// the memory system gives to reads, to writes and to their mixtures.
-//   kProbeAdd    c = a + b per 32-bit lane (two reads, one write: the backward's mixture)
-//   kProbeRead   a is read and summed; the sum is stored only if it equals a value it cannot
-//                take for the fill patterns used, which keeps the loads alive
-//   kProbeWrite  c is filled with a pattern that depends on the position
-constexpr int kProbeAdd = 1, kProbeRead = 2, kProbeWrite = 3;
+// The copy's pattern with NR read streams and NW write streams, to split the copy figure into what
+// the memory system gives to reads, to writes and to the mixtures the row kernels produce.  Every
+// output j is the 32-bit-lane sum of the inputs plus j (a position-dependent pattern without
+// inputs); without outputs the sum is stored only if it equals a value it cannot take for the fill
+// patterns used, which keeps the loads alive.  V vectors per lane and step; the block's waves take
+// consecutive pieces.
+struct ProbeArgs {
+    const u32x4* in[4];
+    u32x4* out[3];
+    int64_t nvec;
+};
 
-template <int MODE, int W, int V>
-__global__ __launch_bounds__(W* kWave) void stream_probe_kernel(const u32x4* __restrict__ a,
-                                                               const u32x4* __restrict__ b,
-                                                               u32x4* __restrict__ c, int64_t nvec) {
+template <int NR, int NW, int V>
+__global__ __launch_bounds__(8 * kWave) void stream_probe_kernel(const ProbeArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int W = blockDim.x >> 6;
     constexpr int64_t kPiece = static_cast<int64_t>(V) * kWave;
-    const int64_t pieces = nvec / kPiece;                 // a tail shorter than one piece is left out
+    constexpr int NQ = NR > 0 ? NR : 1;
+    const int64_t pieces = a.nvec / kPiece;               // a tail shorter than one piece is left out
     const int64_t step = static_cast<int64_t>(gridDim.x) * W;
-    auto fetch = [&](int64_t piece, u32x4 (&qa)[V], u32x4 (&qb)[V]) {
+    auto fetch = [&](int64_t piece, u32x4 (&q)[NQ][V]) {
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            const bool live = piece < pieces;
-            qa[i] = u32x4{0u, 0u, 0u, 0u};
-            qb[i] = u32x4{0u, 0u, 0u, 0u};
-            if (MODE != kProbeWrite && live) qa[i] = __builtin_nontemporal_load(a + piece * kPiece + i * kWave + lane);
-            if (MODE == kProbeAdd && live) qb[i] = __builtin_nontemporal_load(b + piece * kPiece + i * kWave + lane);
+        for (int r = 0; r < NQ; ++r) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                q[r][i] = u32x4{0u, 0u, 0u, 0u};
+                if (r < NR && piece < pieces) q[r][i] = __builtin_nontemporal_load(a.in[r] + piece * kPiece + i * kWave + lane);
+            }
         }
     };
     int64_t piece = static_cast<int64_t>(blockIdx.x) * W + wave;
-    u32x4 ca[V], cb[V], acc = u32x4{0u, 0u, 0u, 0u};
-    fetch(piece, ca, cb);
+    u32x4 cur[NQ][V], acc = u32x4{0u, 0u, 0u, 0u};
+    fetch(piece, cur);
     for (; piece < pieces; piece += step) {
-        u32x4 na[V], nb[V];
-        fetch(piece + step, na, nb);
+        u32x4 nxt[NQ][V];
+        fetch(piece + step, nxt);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < V; ++i) {
-            if (MODE == kProbeRead) {
-                acc += ca[i];
-            } else {
-                const u32x4 v = MODE == kProbeWrite ? u32x4{1u, 2u, static_cast<uint32_t>(i), static_cast<uint32_t>(piece)}
-                                                    : ca[i] + cb[i];
-                __builtin_nontemporal_store(v, c + piece * kPiece + i * kWave + lane);
+            u32x4 v = NR > 0 ? cur[0][i] : u32x4{1u, 2u, static_cast<uint32_t>(i), static_cast<uint32_t>(piece)};
+#pragma unroll
+            for (int r = 1; r < NR; ++r) v += cur[r][i];
+            if (NW == 0) acc += v;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const u32x4 o = v + u32x4{static_cast<uint32_t>(w), 0u, 0u, 0u};
+                __builtin_nontemporal_store(o, a.out[w] + piece * kPiece + i * kWave + lane);
             }
         }
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            ca[i] = na[i];
-            cb[i] = nb[i];
+        for (int r = 0; r < NQ; ++r) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) cur[r][i] = nxt[r][i];
         }
     }
-    if (MODE == kProbeRead && acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) c[lane] = acc;
+    if (NW == 0 && acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u) a.out[0][lane] = acc;
 }
 
 }  // namespace lnmod

@@ -10,6 +10,15 @@ namespace lnmod {
 constexpr int kNumCU = 256;            // MI355X: 8 XCDs x 32 CUs
 constexpr int64_t kMaxD = 8192;
 
+// Launch shape of a row kernel: K waves per row, VPL 16-byte chunks per lane, R rows per block and
+// step, per_cu resident blocks per compute unit that the grid is sized for.
+struct Shape {
+    int K;
+    int VPL;
+    int R;
+    int per_cu;
+};
+
 struct Problem {
     int dtype;                 // LNMOD_BF16 / LNMOD_F32
     const int32_t* cu;         // device segment offsets or nullptr (fixed length)
@@ -18,6 +27,10 @@ struct Problem {
     int64_t T;                 // total tokens
     int64_t D;
     float eps;
+    // Launch shape to use instead of the measured table's entry, or nullptr.  The operator entry
+    // points always pass nullptr; the measurement library's shaped calls pass the caller's shape,
+    // per call, so that a sweep can time candidates without any process-wide state.
+    const Shape* force = nullptr;
 };
 
 // How the token rows are spread over the grid.  `clusters` groups of `nb` blocks each own one
@@ -173,12 +186,6 @@ inline Split choose_split(int nchunks, int dtype) {
 // run.  What the winners share: a wave count that is a multiple of the four SIMDs of a CU (or a
 // single block of 5 or 6 waves), and 16 to 32 KB of row data in flight per CU.  Neighbouring
 // widths do not share winners: an entry that is best at D = 4096 loses 28 % at D = 3584.
-struct Shape {
-    int K;
-    int VPL;
-    int R;
-    int per_cu;
-};
 
 // Entry of a per-512-features table (index 1 ... 16; [0] is unused).  A row of at most 64 chunks
 // on a single wave needs one chunk per lane whatever the first entry says.
@@ -238,7 +245,7 @@ inline Shape bwd_shape(int nchunks, int dtype) {
 }
 
 // Backward that forms the statistics again from x.  It has one more dependent chain per step
-// (pivot, four wave sums, the merge with a division and a square root), which fewer waves per
+// (per-wave mean, four wave sums, the merge with a division and a square root), which fewer waves per
 // row with more chunks each, or two blocks per CU, hide better than the shapes above; timed at
 // D = 512 ... 8192 like the tables above; it then runs 2 to 20 % behind the backward that reads
 // the saved statistics (D = 5120: 14 %).
@@ -261,14 +268,9 @@ inline Shape rc_bwd_shape(int nchunks, int dtype) {
     return table_entry(tab32, nchunks, dtype);
 }
 
-// Tuning interface (include/lnmod_tuning.h): a process-wide override of one kernel family's launch
-// shape, used by the shape sweep that produced the tables above.  An override that does not cover
-// the row makes the launch fail instead of computing on part of the row.
-enum TuneFamily { kTuneFwd = 0, kTuneBwd, kTuneBwdRecompute, kTuneTokFwd, kTuneTokBwd, kTuneGatedFwd, kTuneGatedBwd,
-                  kTuneQkFwd, kTuneQkBwd, kTuneFamilies };
-extern Shape g_tune_shape[kTuneFamilies];                 // K == 0: no override
-
-inline Shape tuned(TuneFamily f, Shape table) { return g_tune_shape[f].K > 0 ? g_tune_shape[f] : table; }
+// The table's entry, or the shape the call carries (Problem::force).  A forced shape that does not
+// cover the row makes the launch fail instead of computing on part of the row.
+inline Shape pick_shape(const Shape* force, Shape table) { return force ? *force : table; }
 inline bool covers(const Shape& s, int nchunks) { return s.K * s.VPL * 64 >= nchunks; }
 
 // Per-token modulation (three input streams forward; three in, three out backward).  bf16: a table
@@ -317,8 +319,11 @@ inline Shape tok_bwd_shape(int nchunks, int dtype) {
 
 // The backward's plan for this problem: the same function sizes the workspace, drives the main
 // kernel's grid and tells the second pass which partial-sum slots belong to a segment.
-RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute);
-inline int64_t bwd_slots(const RowPlan& p, int64_t nseg) { return (p.clusters + nseg) * p.nb; }
+RowPlan bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype, bool recompute, const Shape* force = nullptr);
+// Slot of (cluster c, segment m, member j) is (c + m) * nb + j with c < clusters, m < nseg.
+inline int64_t bwd_slots(const RowPlan& p, int64_t nseg) {
+    return nseg < 1 ? 0 : (p.clusters + nseg - 1) * p.nb;
+}
 
 // Shape of the second pass: V features per lane, W waves per block.  Wide lanes need enough
 // (segment, sum, feature-block) triples to fill the chip; a wave should have about four slots
@@ -338,6 +343,10 @@ inline ReduceShape reduce_shape(int64_t nseg, int nsum, int64_t D, int64_t clust
     return sh;
 }
 
+// Text naming the kernel instantiations and grids that a call with these arguments launches.
+int describe_fwd(const Problem& p, bool per_token, char* buf, size_t n);
+int describe_bwd(const Problem& p, bool per_token, bool recompute, char* buf, size_t n);
+
 struct ReduceArgs;
 hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st);
 
@@ -354,7 +363,9 @@ hipError_t launch_bwd_tok(const Problem& p, const void* dy, const void* x, const
 hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* xhat, void* y, float* mean, float* rstd, hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
-hipError_t launch_stream_probe(const void* a, const void* b, void* c, size_t bytes, int mode, hipStream_t st);
+bool probe_mixture_supported(int reads, int writes);
+hipError_t launch_stream_probe(const void* const* in, int reads, void* const* out, int writes, size_t bytes,
+                               int blocks, int waves, int vecs, hipStream_t st);
 
 // Gated residual + LayerNorm-Modulate (per-sample / per-segment gate, shift, scale).
 RowPlan gated_bwd_plan(int64_t T, int64_t nseg, int64_t D, int dtype);

@@ -52,10 +52,10 @@ Shape wide_table_shape(int nchunks, int dtype, bool backward) {
     return sh;
 }
 
-// The table's shape or the tuning override; ok is false for an override these kernels are not
-// compiled for or that does not cover the row.
+// The table's shape; ok is false for a shape these kernels are not compiled for or that does not
+// cover the row (a mistake in the table then fails the launch instead of computing on part of a row).
 Shape wide_shape(int nchunks, int dtype, bool backward, bool* ok) {
-    const Shape sh = tuned(backward ? kTuneQkBwd : kTuneQkFwd, wide_table_shape(nchunks, dtype, backward));
+    const Shape sh = wide_table_shape(nchunks, dtype, backward);
     const int wide = dtype == 0 ? 2 : 4;
     bool compiled;
     if (sh.K == 1) compiled = sh.VPL >= 1 && (sh.VPL <= 3 || (dtype == 1 && (sh.VPL == 4 || sh.VPL == 6)));

@@ -5,7 +5,7 @@
 
 #include "lnmod.h"
 #include "lnmod_sched.h"
-#include "lnmod_tuning.h"
+#include "lnmod_tools.h"
 
 int main(void) {
     int shape[4] = {0, 0, 0, 0};
@@ -15,9 +15,12 @@ int main(void) {
         return 1;
     if (strcmp(lnmod_status_string(LNMOD_OK), lnmod_status_string(LNMOD_EINVAL)) == 0) return 2;
     if (lnmod_backward_workspace_bytes(1, 75600, 5120, LNMOD_PER_SAMPLE) == 0) return 3;
-    if (lnmod_tuning_table_shape(LNMOD_TUNE_BACKWARD, 5120, LNMOD_BF16, shape) != LNMOD_OK) return 4;
+    if (lnmod_table_shape(LNMOD_FAMILY_BACKWARD, 5120, LNMOD_BF16, 0, shape) != LNMOD_OK) return 4;
     if (shape[0] * shape[1] * 64 < 5120 / 8) return 5;
-    if (lnmod_tuning_set_shape(LNMOD_TUNE_FORWARD, 0, 0, 0, 0) != LNMOD_OK) return 6;
+    if (lnmod_backward_workspace_bytes_shaped(NULL, 1, 75600, 5120, LNMOD_PER_SAMPLE) !=
+        lnmod_backward_workspace_bytes(1, 75600, 5120, LNMOD_PER_SAMPLE))
+        return 6;
+    if (lnmod_backward_workspace_bytes_shaped(shape, 1, 75600, 5120, LNMOD_PER_SAMPLE) == 0) return 7;
     printf("backward D=5120 bf16: K=%d VPL=%d R=%d per_cu=%d\n", shape[0], shape[1], shape[2], shape[3]);
     return 0;
 }

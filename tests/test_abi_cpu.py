@@ -9,7 +9,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "lnmod.h")
 
-from paper_2605_17923_amd import lnmod  # noqa: E402
+from paper_2605_17923_amd import lnmod, lnmod_tools  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -26,11 +26,25 @@ def declared_functions():
     return sorted(set(re.findall(r"\b(lnmod_[a-z_0-9]+)\s*\(", text)))
 
 
+def dynamic_symbols(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    return sorted(line.split()[-1] for line in out.splitlines() if line.strip())
+
+
 def test_header_symbols_are_exported(lib):
     names = declared_functions()
     assert set(names) == set(lnmod.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_operator_library_exports_the_operator_and_scheduler_entry_points_only(lib):
+    """No measurement or tuning entry, no C++ symbol and no variable leaves liblnmod.so."""
+    sched = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "lnmod_sched.h")).read(), flags=re.S)
+    sched_names = set(re.findall(r"\b(lnmod_[a-z_0-9]+)\s*\(", sched))
+    assert sched_names
+    assert set(dynamic_symbols(lnmod.LIBRARY)) == set(declared_functions()) | sched_names
 
 
 def test_binding_mirrors_every_entry_point():
@@ -141,25 +155,6 @@ def test_workspace_query(lib):
     assert q(1, 10, 5120, 0) <= n
 
 
-def test_copy_and_unfused_reject_bad_arguments(lib):
-    assert lnmod.lnmod_copy(None, A, 64, None) == lnmod.LNMOD_EINVAL
-    assert lnmod.lnmod_copy(A, A, 60, None) == lnmod.LNMOD_EINVAL
-    assert lnmod.lnmod_copy(A + 4, A, 64, None) == lnmod.LNMOD_EALIGN
-    assert lnmod.lnmod_copy(A, A, 0, None) == lnmod.LNMOD_OK
-    probe = lnmod.lnmod_stream_probe
-    assert probe(A, A, A, 4096, 0, None) == lnmod.LNMOD_EINVAL                 # no such mode
-    assert probe(A, None, A, 4096, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EINVAL
-    assert probe(None, None, A, 4096, lnmod.LNMOD_PROBE_READ, None) == lnmod.LNMOD_EINVAL
-    assert probe(A, None, A, 512, lnmod.LNMOD_PROBE_READ, None) == lnmod.LNMOD_EINVAL
-    assert probe(None, None, None, 4096, lnmod.LNMOD_PROBE_WRITE, None) == lnmod.LNMOD_EINVAL
-    assert probe(A, A, A, 4100, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EINVAL
-    assert probe(A, A, A + 8, 4096, lnmod.LNMOD_PROBE_ADD, None) == lnmod.LNMOD_EALIGN
-    assert probe(None, None, None, 0, lnmod.LNMOD_PROBE_WRITE, None) == lnmod.LNMOD_OK
-    u = lnmod.lnmod_unfused_forward
-    assert u(A, A, A, 2, 4, 64, 1e-6, None, None, A, A, A, 0) == lnmod.LNMOD_EINVAL
-    assert u(A, A, A, 2, 4, 63, 1e-6, None, A, A, A, A, 0) == lnmod.LNMOD_EUNSUPPORTED
-
-
 def gfwd(x=A, u=A, gate=A, shift=A, scale=A, cu=None, n=2, s=4, D=64, eps=1e-6, h=A, y=A, mean=A,
          rstd=A, dtype=0):
     return lnmod.lnmod_gated_forward(x, u, gate, shift, scale, cu, n, s, D, eps, None, h, y, mean,
@@ -190,10 +185,6 @@ def test_gated_rejects_bad_arguments(lib):
     assert gbwd(ws=None) == E.LNMOD_EWORKSPACE and gbwd(ws_bytes=16) == E.LNMOD_EWORKSPACE
     assert gbwd(ws=A + 4) == E.LNMOD_EALIGN
     assert gbwd(n=0, s=0) == E.LNMOD_OK
-    g = lnmod.lnmod_gate_residual
-    assert g(A, None, A, 2, 4, 64, None, A, 0) == E.LNMOD_EINVAL
-    assert g(A, A, A, 2, 4, 60, None, A, 0) == E.LNMOD_EUNSUPPORTED
-    assert g(A, A, A + 1, 2, 4, 64, None, A, 0) == E.LNMOD_EALIGN
 
 
 def test_gated_workspace_query(lib):
@@ -236,46 +227,111 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         lnmod.lnmod_forward(A, A, A, 1, 1, 64, 1e-6, None, A, A, A, 0, 0)
 
 
-# ---- tuning interface (include/lnmod_tuning.h)
+# ---- the measurement library (include/lnmod_tools.h)
 
-TUNING_HEADER = os.path.join(ROOT, "include", "lnmod_tuning.h")
+TOOLS_HEADER = os.path.join(ROOT, "include", "lnmod_tools.h")
+T = lnmod_tools
 
 
-def test_tuning_header_symbols_are_exported(lib):
-    text = re.sub(r"/\*.*?\*/", "", open(TUNING_HEADER).read(), flags=re.S)
+@pytest.fixture(scope="module")
+def tools(lib):
+    return lnmod_tools.library()
+
+
+def test_tools_header_symbols_are_exported(tools):
+    text = re.sub(r"/\*.*?\*/", "", open(TOOLS_HEADER).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(lnmod_[a-z_0-9]+)\s*\(", text)))
-    assert set(names) == set(lnmod.TUNING_EXPORTS)
+    assert set(names) == set(lnmod_tools.EXPORTS)
+    assert set(dynamic_symbols(lnmod_tools.LIBRARY)) == set(names)
     for n in names:
-        assert hasattr(lib, n), n
-        assert callable(getattr(lnmod, n)), n
+        assert hasattr(tools, n), n
+        assert callable(getattr(lnmod_tools, n)), n
 
 
-def test_tuning_set_shape_validation(lib):
-    ok = lnmod.lnmod_tuning_set_shape
-    try:
-        assert ok(-1, 1, 1, 1, 1) == 1 and ok(lnmod.LNMOD_TUNE_FAMILIES, 1, 1, 1, 1) == 1
-        for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
-                    (1, 1, 1, 0), (1, 1, 1, 17)):
-            assert ok(lnmod.LNMOD_TUNE_FORWARD, *bad) == 1, bad
-        assert ok(lnmod.LNMOD_TUNE_FORWARD, 4, 3, 1, 2) == 0
-    finally:
-        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
-            assert ok(fam, 0, 0, 0, 0) == 0
+def test_copy_probe_and_comparators_reject_bad_arguments(tools):
+    E = lnmod
+    assert T.lnmod_copy(None, A, 64, None) == E.LNMOD_EINVAL
+    assert T.lnmod_copy(A, A, 60, None) == E.LNMOD_EINVAL
+    assert T.lnmod_copy(A + 4, A, 64, None) == E.LNMOD_EALIGN
+    assert T.lnmod_copy(A, A, 0, None) == E.LNMOD_OK
+    probe = T.lnmod_stream_probe
+    assert probe([A, A, A, A, A], [A], 4096, None) == E.LNMOD_EINVAL           # no such mixture
+    assert probe([A, A], [A, A], 4096, None) == E.LNMOD_EINVAL
+    assert probe([A, None], [A], 4096, None) == E.LNMOD_EINVAL
+    assert probe([A], [None], 4096, None, writes=0) == E.LNMOD_EINVAL
+    assert probe([A], [A], 512, None, writes=0) == E.LNMOD_EINVAL             # out[0] must hold 1 KB
+    assert probe([A, A], [A], 4100, None) == E.LNMOD_EINVAL
+    assert probe([A, A], [A + 8], 4096, None) == E.LNMOD_EALIGN
+    assert probe([A, A], [A], 4096, None, launch=(256, 9, 4)) == E.LNMOD_EINVAL
+    assert probe([A, A], [A], 4096, None, launch=(256, 4, 3)) == E.LNMOD_EINVAL
+    assert probe([A, A], [A], 4096, None, launch=(0, 4, 4)) == E.LNMOD_EINVAL
+    assert probe([], [A], 0, None) == E.LNMOD_OK
+    for nr, nw in T.PROBE_MIXTURES:
+        assert probe([A] * nr, [A] * max(nw, 1), 0, None, writes=nw) == E.LNMOD_OK
+    u = T.lnmod_unfused_forward
+    assert u(A, A, A, 2, 4, 64, 1e-6, None, None, A, A, A, 0) == E.LNMOD_EINVAL
+    assert u(A, A, A, 2, 4, 63, 1e-6, None, A, A, A, A, 0) == E.LNMOD_EUNSUPPORTED
+    g = T.lnmod_gate_residual
+    assert g(A, None, A, 2, 4, 64, None, A, 0) == E.LNMOD_EINVAL
+    assert g(A, A, A, 2, 4, 60, None, A, 0) == E.LNMOD_EUNSUPPORTED
+    assert g(A, A, A + 1, 2, 4, 64, None, A, 0) == E.LNMOD_EALIGN
 
 
-def test_tuning_table_shape_matches_the_documented_entries(lib):
+def sfwd(shape, x=A, shift=A, scale=A, cu=None, B=2, S=4, D=64, eps=1e-6, y=A, mean=A, rstd=A, dtype=0, mod=0):
+    return T.lnmod_forward_shaped(shape, x, shift, scale, cu, B, S, D, eps, None, y, mean, rstd, dtype, mod)
+
+
+def sbwd(shape, dy=A, x=A, scale=A, cu=None, B=2, S=4, D=64, eps=1e-6, mean=A, rstd=A, dx=A, dshift=A, dscale=A,
+         ws=A, ws_bytes=1 << 40, dtype=0, mod=0):
+    return T.lnmod_backward_shaped(shape, dy, x, scale, cu, B, S, D, eps, None, mean, rstd, dx, dshift, dscale,
+                                   ws, ws_bytes, dtype, mod)
+
+
+def test_shaped_calls_validate_the_shape_and_then_like_the_operator_calls(tools):
+    E = lnmod
+    for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (0, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
+                (1, 1, 1, 0), (1, 1, 1, 17)):
+        assert sfwd(bad) == E.LNMOD_EINVAL, bad
+        assert sbwd(bad) == E.LNMOD_EINVAL, bad
+        assert T.lnmod_backward_workspace_bytes_shaped(bad, 1, 100, 64, 0) == 0
+        assert T.lnmod_describe_launch(False, bad, 1, 100, False, 64, 0, 0) == ""
+    ok = (1, 1, 1, 4)
+    assert sfwd(ok, x=None) == E.LNMOD_EINVAL and sfwd(ok, D=63) == E.LNMOD_EUNSUPPORTED
+    assert sfwd(ok, y=A + 4) == E.LNMOD_EALIGN and sfwd(ok, S=0) == E.LNMOD_OK
+    assert sfwd(ok, cu=A, mod=1) == E.LNMOD_EINVAL                  # packed batches are per segment
+    assert sbwd(ok, dx=None) == E.LNMOD_EINVAL and sbwd(ok, ws=None) == E.LNMOD_EWORKSPACE
+    assert sbwd(ok, ws_bytes=16) == E.LNMOD_EWORKSPACE and sbwd(None, ws_bytes=16) == E.LNMOD_EWORKSPACE
+    assert T.lnmod_backward_workspace_bytes_shaped(None, 1, 75600, 5120, 0) == \
+        lnmod.lnmod_backward_workspace_bytes(1, 75600, 5120, 0)
+    # the workspace follows the shape: twice the blocks per CU, twice the slots
+    one = T.lnmod_backward_workspace_bytes_shaped((4, 3, 2, 1), 1, 75600, 5120, 0)
+    two = T.lnmod_backward_workspace_bytes_shaped((4, 3, 2, 2), 1, 75600, 5120, 0)
+    assert one == 256 * 2 * 5120 * 4 and two == 2 * one
+
+
+def test_a_shape_that_does_not_cover_the_row_fails_before_any_launch(tools):
+    small = (1, 1, 1, 4)                                           # 64 chunks: 512 bf16 features
+    assert sfwd(small, D=520, B=1, S=8) == 5
+    assert sfwd(small, D=520, B=1, S=8, mod=1) == 5
+    assert sbwd(small, D=520, B=1, S=8) == 5
+    assert sbwd(small, D=520, B=1, S=8, mean=None, rstd=None) == 5
+    assert sbwd(small, D=520, B=1, S=8, mod=1, ws=None, ws_bytes=0) == 5
+
+
+def test_table_shape_matches_the_documented_entries(tools):
     # bf16 D = 5120 (the headline width) and D = 1536, as the design notes list them
-    get = lnmod.lnmod_tuning_table_shape
-    assert get(lnmod.LNMOD_TUNE_FORWARD, 5120, 0) == (0, (5, 2, 2, 1))
-    assert get(lnmod.LNMOD_TUNE_BACKWARD, 5120, 0) == (0, (4, 3, 2, 1))
-    assert get(lnmod.LNMOD_TUNE_BACKWARD_RECOMPUTE, 5120, 0) == (0, (4, 3, 1, 2))
-    assert get(lnmod.LNMOD_TUNE_FORWARD, 1536, 0) == (0, (1, 3, 2, 4))
-    assert get(lnmod.LNMOD_TUNE_GATED_FORWARD, 5120, 0) == (0, (4, 3, 1, 1))
-    assert get(lnmod.LNMOD_TUNE_GATED_BACKWARD, 5120, 0) == (0, (8, 2, 1, 1))
-    assert get(lnmod.LNMOD_TUNE_FAMILIES, 5120, 0)[0] == 1 and get(0, 5120, 2)[0] == 1
+    get = T.lnmod_table_shape
+    assert get(T.LNMOD_FAMILY_FORWARD, 5120, 0) == (0, (5, 2, 2, 1))
+    assert get(T.LNMOD_FAMILY_BACKWARD, 5120, 0) == (0, (4, 3, 2, 1))
+    assert get(T.LNMOD_FAMILY_BACKWARD_RECOMPUTE, 5120, 0) == (0, (4, 3, 1, 2))
+    assert get(T.LNMOD_FAMILY_FORWARD, 1536, 0) == (0, (1, 3, 2, 4))
+    assert get(T.LNMOD_FAMILY_FORWARD, 1536, 0, tokens=200000) == (0, (1, 3, 2, 3))
+    assert get(T.LNMOD_FAMILY_GATED_FORWARD, 5120, 0) == (0, (4, 3, 1, 1))
+    assert get(T.LNMOD_FAMILY_GATED_BACKWARD, 5120, 0) == (0, (8, 2, 1, 1))
+    assert get(T.LNMOD_FAMILIES, 5120, 0)[0] == 1 and get(0, 5120, 2)[0] == 1
     assert get(0, 5124, 0)[0] == 2 and get(0, 8200, 1)[0] == 2
     # every family's entry covers its row, at every supported width and both types
-    for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
+    for fam in range(T.LNMOD_FAMILIES):
         for dtype, vec in ((0, 8), (1, 4)):
             for D in range(8, 8193, 8):
                 st, (K, VPL, R, per_cu) = get(fam, D, dtype)
@@ -283,15 +339,15 @@ def test_tuning_table_shape_matches_the_documented_entries(lib):
                 assert K * VPL * 64 >= D // vec and R in (1, 2) and per_cu >= 1, (fam, dtype, D)
 
 
-def test_override_that_does_not_cover_the_row_fails_before_any_launch(lib):
-    try:
-        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
-            assert lnmod.lnmod_tuning_set_shape(fam, 1, 1, 1, 4) == 0      # 64 chunks: 512 bf16 features
-        assert fwd(D=520, B=1, S=8) == 5
-        assert fwd(D=520, B=1, S=8, mod=1) == 5
-        assert bwd(D=520, B=1, S=8) == 5
-        assert bwd(D=520, B=1, S=8, mean=None, rstd=None) == 5
-        assert bwd(D=520, B=1, S=8, mod=1, ws=None, ws_bytes=0) == 5
-    finally:
-        for fam in range(lnmod.LNMOD_TUNE_FAMILIES):
-            lnmod.lnmod_tuning_set_shape(fam, 0, 0, 0, 0)
+def test_describe_launch_names_the_kernels_of_the_headline_workload(tools):
+    d = T.lnmod_describe_launch
+    assert d(False, None, 1, 75600, False, 5120, 0, 0) == \
+        "fwd_split_kernel<bf16_io, 2, 5, 2, true, 0, true> grid=256 block=320 clusters=1"
+    assert d(True, None, 1, 75600, False, 5120, 0, 0) == \
+        ("bwd_seg_kernel<bf16_io, 3, 4, 2, false, false, true, false> grid=256 block=256 clusters=1"
+         " + bwd_reduce_kernel<1> grid=160 block=1024 slots=256")
+    assert "true, true>" in d(True, None, 1, 75600, False, 5120, 0, 0, recompute=True)
+    assert d(True, None, 2, 32760, False, 5120, 0, 1).startswith("bwd_seg_kernel<bf16_io, 2, 5, 1, true, true, true, false>")
+    assert "reduce" not in d(True, None, 2, 32760, False, 5120, 0, 1)
+    assert d(False, (4, 3, 1, 2), 1, 75600, False, 5120, 0, 0).startswith("fwd_split_kernel<bf16_io, 3, 4, 1, false, 0, true> grid=512")
+    assert d(False, None, 1, 0, False, 5120, 0, 0) == "" and d(False, None, 1, 10, False, 5121, 0, 0) == ""

@@ -3,9 +3,9 @@ against the float64 oracle in oracle/gated_oracle.c on the same seeded inputs.
 
 h is a quantised value (one fp32 fused multiply-add rounded to the I/O type), so both sides take
 that rounding in the same precision and h is compared bit for bit; y, the statistics and every
-gradient are compared with the tolerances of the LayerNorm-Modulate tests.  The backward is fed
-the h, mean and rstd the GPU forward produced; the oracle reads the same h and recomputes the
-statistics in float64."""
+gradient are compared with the tolerances of the LayerNorm-Modulate tests.  The GPU backward is fed
+the h, mean and rstd the GPU forward produced; the oracle's backward reads the oracle's own h and
+recomputes the statistics in float64, so no GPU output enters the expected values."""
 import numpy as np
 import pytest
 import torch
@@ -45,29 +45,24 @@ def run_gated(inp, seed, sample_rows=None, label=""):
 
     rows = np.arange(T) if sample_rows is None else np.asarray(sample_rows, dtype=np.int64)
     rows_t = torch.from_numpy(rows).cuda()
-    seg_of = np.searchsorted(cu64, rows, side="right") - 1
-    if sample_rows is None:
-        h64, y64, mean64, rstd64 = go.forward(inp.x, ex.u, ex.gate, inp.shift, inp.scale, w.eps, cu=cu64,
-                                              quant=quant)
-    else:                                   # rows are independent in the forward
-        h64, y64 = np.empty((rows.size, D)), np.empty((rows.size, D))
-        mean64, rstd64 = np.empty(rows.size), np.empty(rows.size)
-        for m in np.unique(seg_of):
-            sel = np.nonzero(seg_of == m)[0]
-            a, b, c, d = go.forward(inp.x[rows[sel]], ex.u[rows[sel]], ex.gate[m:m + 1], inp.shift[m:m + 1],
-                                    inp.scale[m:m + 1], w.eps, B=1, S=sel.size, quant=quant)
-            h64[sel], y64[sel], mean64[sel], rstd64[sel] = a, b, c, d
-    h_got = to_host64(h.reshape(T, D)[rows_t])
+    h64, y64, mean64, rstd64 = go.forward(inp.x, ex.u, ex.gate, inp.shift, inp.scale, w.eps, cu=cu64, quant=quant)
     if dt == "bf16":
-        assert np.array_equal(h_got, h64), "h: %d elements differ from the rounded reference" % int(
-            (h_got != h64).sum())
+        # Every row, on the device (h64 holds bf16 values exactly).  The oracle rounds its float64 sum to
+        # float32 and then to bf16, because one fp32 fused multiply-add followed by one store rounding is
+        # what "h as stored" means for an fp32 kernel: a reading that follows the arithmetic type of the
+        # path, taken because the paper only names the "Gate + Norm" fusion (Sec. 4.4) and defines nothing.
+        h_ref = torch.from_numpy(h64).to(torch.bfloat16).cuda()
+        differ = int((h.reshape(T, D) != h_ref).sum())
+        assert differ == 0, "h: %d elements differ from the rounded reference" % differ
+        del h_ref
     else:
         # fp32: the float64 sum of a 48-bit product and a 24-bit addend can itself round
+        h_got = to_host64(h.reshape(T, D))
         ulp = np.spacing(np.abs(h64).astype(np.float32)).astype(np.float64)
         assert np.all(np.abs(h_got - h64) <= ulp), "h: beyond one float32 ulp"
         assert np.mean(h_got != h64) < 1e-4
-    check_io_tensor("y", y.reshape(T, D)[rows_t], y64, dt)
-    check_stats(mean.reshape(T)[rows_t], rstd.reshape(T)[rows_t], mean64, rstd64)
+    check_io_tensor("y", y.reshape(T, D)[rows_t], y64[rows], dt)
+    check_stats(mean.reshape(T)[rows_t], rstd.reshape(T)[rows_t], mean64[rows], rstd64[rows])
 
     if w.varlen:
         dx, du, dgate, dsh, dsc = lnmod.gated_backward(dy, dh, h, u, gate, scale, mean, rstd, cu_dev, w.eps)
@@ -76,13 +71,20 @@ def run_gated(inp, seed, sample_rows=None, label=""):
         dx, du, dgate, dsh, dsc = lnmod.gated_backward(v(dy), v(dh), v(h), v(u), gate, scale, mean, rstd,
                                                        None, w.eps)
     torch.cuda.synchronize()
-    h_host = h.reshape(T, D).to(torch.float32).cpu().numpy()        # exactly what the GPU backward read
-    dx64, du64, dg64, dsh64, dsc64 = go.backward(inp.dy, ex.dh, h_host, ex.u, ex.gate, inp.scale, w.eps, cu=cu64)
+    # the oracle's backward reads the oracle's h (for bf16 the GPU's h was just shown to be the same bits)
+    dx64, du64, dg64, dsh64, dsc64 = go.backward(inp.dy, ex.dh, h64, ex.u, ex.gate, inp.scale, w.eps, cu=cu64)
     check_io_tensor("dx", dx.reshape(T, D)[rows_t], dx64[rows], dt)
     check_io_tensor("du", du.reshape(T, D)[rows_t], du64[rows], dt)
     check_f32_tensor("dgate", dgate, dg64)
     check_f32_tensor("dshift", dsh, dsh64)
     check_f32_tensor("dscale", dsc, dsc64)
+    if dt != "bf16":
+        # fp32: the GPU backward read its own h, up to one float32 ulp from the oracle's on a few elements.
+        # Bound what that is worth: the oracle's backward on the GPU's h moves no gradient by more than a
+        # tenth of the tolerance above.
+        alt = go.backward(inp.dy, ex.dh, h.reshape(T, D).cpu().numpy(), ex.u, ex.gate, inp.scale, w.eps, cu=cu64)
+        for name, a_, b_ in zip(("dx", "du", "dgate", "dshift", "dscale"), alt, (dx64, du64, dg64, dsh64, dsc64)):
+            check_f32_tensor(name + " (effect of h within one ulp)", a_, b_, rel=1e-6)
 
 
 def test_gated_tiny_fp32():

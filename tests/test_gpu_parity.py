@@ -7,8 +7,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2605_17923_amd import lnmod, synth
-from parity_util import check_f32_tensor, check_io_tensor, check_stats, to_device
+from paper_2605_17923_amd import lnmod, lnmod_tools, synth
+from parity_util import ChunkedCheck, check_f32_tensor, check_io_tensor, check_stats, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -221,6 +221,37 @@ def test_recompute_backward_degenerate_rows():
     run_case(inp, label="recompute degenerate rows", recompute=True)
 
 
+@pytest.mark.parametrize("dtype,D", [("f32", 5120), ("bf16", 5120), ("f32", 1536), ("bf16", 1536), ("f32", 8192),
+                                     ("bf16", 3080)])
+def test_recompute_backward_rows_whose_parts_do_not_resemble_the_row(dtype, D):
+    # The recomputing backward centres every wave's sums on that wave's own mean and merges the waves'
+    # results; rows on which a part of the row says little about the whole are where a cheaper centre
+    # (a few sampled elements) or a one-pass E[x^2] - mean^2 would lose rstd's fifth digit:
+    #   0  a step along D: first half near 0, second half near 10
+    #   1  mean 100 standard deviations away from zero
+    #   2  a nearly constant row with large values exactly at the first element of every 16-byte chunk
+    #      of the first chunk column (the elements a sampled centre would look at)
+    #   3  one quarter of the row shifted by 1000 standard deviations of the rest
+    #   4  mean -100 standard deviations, tiny spread
+    # The saved-statistics path runs on the same rows for comparison.
+    inp = synth.make_inputs(0, B=1, S=9, D=D, dtype=dtype, seed=77)
+    rng = np.random.default_rng(78)
+    x = inp.x
+    x[0] = 0.01 * rng.standard_normal(D)
+    x[0, D // 2:] += 10.0
+    x[1] = 100.0 + rng.standard_normal(D)
+    x[2] = 1e-3 * rng.standard_normal(D)
+    E = 8 if dtype == "bf16" else 4
+    x[2, 0:min(D, 64 * E * 16):E] = 100.0
+    x[3] = 0.05 * rng.standard_normal(D)
+    x[3, D // 4:D // 2] += 50.0
+    x[4] = -7.0 + 0.07 * rng.standard_normal(D)
+    if dtype == "bf16":
+        inp.x[:] = synth.round_to_bf16(x)
+    run_case(inp, label="unrepresentative parts, recompute, D=%d %s" % (D, dtype), recompute=True)
+    run_case(inp, label="unrepresentative parts, saved statistics, D=%d %s" % (D, dtype))
+
+
 # ---- random shapes --------------------------------------------------------------------------------
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes(seed):
@@ -251,41 +282,89 @@ def test_random_shapes(seed):
 
 
 # ---- full-size workloads in the benchmark's launch configuration --------------------------------
-def _sample_rows(T, cu, n=1500, seed=7):
-    rng = np.random.default_rng(seed)
-    rows = set(rng.integers(0, T, n).tolist())
-    rows.update([0, 1, 2, 3, T - 1, T - 2, T - 3, T - 4])
-    for c in np.asarray(cu, dtype=np.int64):
-        for d in (-2, -1, 0, 1):
-            if 0 <= c + d < T:
-                rows.add(int(c + d))
-    return np.array(sorted(rows), dtype=np.int64)
+def run_case_full(inp, recompute=False, chunk=16384):
+    """A full-size workload through the C ABI, EVERY row of every output against the oracle.
+    The forward oracle runs in row chunks (rows are independent; a chunk never crosses a segment),
+    the backward oracle once on the whole batch; the comparison itself runs on the device
+    (parity_util.ChunkedCheck)."""
+    w = inp.workload
+    dt = w.dtype
+    T, D, B = inp.T, inp.D, inp.B
+    per_token = w.mod == synth.PER_TOKEN
+    print("full-size case", w.name, "dtype", dt, "T", T, "D", D, "B", B, "varlen", w.varlen, "recompute", recompute,
+          flush=True)
+    x, shift, scale = to_device(inp.x, dt), to_device(inp.shift, dt), to_device(inp.scale, dt)
+    cu64 = inp.cu_seqlens.astype(np.int64)
+    cu_dev = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+    if w.varlen:
+        y, mean, rstd = lnmod.forward_varlen(x, shift, scale, cu_dev, w.eps)
+    else:
+        S = inp.S
+        y, mean, rstd = lnmod.forward(x.view(B, S, D), shift.view(B, S, D) if per_token else shift,
+                                      scale.view(B, S, D) if per_token else scale, w.eps)
+    torch.cuda.synchronize()
+    y, mean, rstd = y.reshape(T, D), mean.reshape(T), rstd.reshape(T)
+    ck = ChunkedCheck("y", dt)
+    bounds = [(0, T)] if per_token else [(int(cu64[m]), int(cu64[m + 1])) for m in range(B)]
+    for m, (lo, hi) in enumerate(bounds):
+        for a in range(lo, hi, chunk):
+            b = min(hi, a + chunk)
+            if per_token:
+                y64, mean64, rstd64 = oracle.forward(inp.x[a:b], inp.shift[a:b], inp.scale[a:b], w.eps, B=1, S=b - a,
+                                                     mod=oracle.PER_TOKEN)
+            else:
+                y64, mean64, rstd64 = oracle.forward(inp.x[a:b], inp.shift[m:m + 1], inp.scale[m:m + 1], w.eps,
+                                                     B=1, S=b - a)
+            ck.add(y[a:b], y64)
+            check_stats(mean[a:b], rstd[a:b], mean64, rstd64)
+    assert ck.rows == T
+    print("  y rel-L2 %.3e over %d rows" % (ck.finish(), ck.rows), flush=True)
+    if inp.dy is None:
+        return
+    dy = to_device(inp.dy, dt)
+    stats = (None, None) if recompute else (mean, rstd)
+    if w.varlen:
+        dx, dsh, dsc = lnmod.backward_varlen(dy, x, scale, cu_dev, stats[0], stats[1], w.eps)
+    else:
+        dx, dsh, dsc = lnmod.backward(dy.view(B, S, D), x.view(B, S, D), scale.view(B, S, D) if per_token else scale,
+                                      stats[0], stats[1], w.eps)
+    torch.cuda.synchronize()
+    omod = oracle.PER_TOKEN if per_token else oracle.PER_SEGMENT
+    dx64, dsh64, dsc64 = oracle.backward(inp.dy, inp.x, inp.scale, w.eps, cu=cu64, mod=omod)
+    pairs = [("dx", dx.reshape(T, D), dx64)]
+    if per_token:
+        pairs += [("dshift", dsh.reshape(T, D), dsh64), ("dscale", dsc.reshape(T, D), dsc64)]
+    else:
+        check_f32_tensor("dshift", dsh, dsh64)
+        check_f32_tensor("dscale", dsc, dsc64)
+    for name, got, ref in pairs:
+        ck = ChunkedCheck(name, dt)
+        for a in range(0, T, chunk):
+            ck.add(got[a:a + chunk], ref[a:a + chunk])
+        assert ck.rows == T
+        print("  %s rel-L2 %.3e over %d rows" % (name, ck.finish(), ck.rows), flush=True)
 
 
 def test_config1_full_size():
-    inp = synth.make_inputs(1)
-    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+    run_case_full(synth.make_inputs(1))
 
 
 def test_config2_full_size():
-    inp = synth.make_inputs(2)
-    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+    run_case_full(synth.make_inputs(2))
 
 
 def test_config2_full_size_recompute_backward():
-    inp = synth.make_inputs(2)
-    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens), recompute=True)
+    run_case_full(synth.make_inputs(2), recompute=True)
 
 
 def test_config3_full_size():
-    inp = synth.make_inputs(3)
-    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+    run_case_full(synth.make_inputs(3))
 
 
 def test_config4_full_size():
     inp = synth.make_inputs(4)
     assert 140_000 <= inp.T <= 160_000 and inp.B == 24
-    run_case(inp, sample_rows=_sample_rows(inp.T, inp.cu_seqlens))
+    run_case_full(inp)
 
 
 def test_tensors_beyond_4_gib():
@@ -500,7 +579,7 @@ def test_unfused_comparator_and_copy_match():
     mean = torch.empty(inp.T, device="cuda")
     rstd = torch.empty(inp.T, device="cuda")
     s = torch.cuda.current_stream().cuda_stream
-    assert lnmod.lnmod_unfused_forward(x, shift, scale, 1, inp.T, inp.D, 1e-6, s, tmp, y, mean, rstd,
+    assert lnmod_tools.lnmod_unfused_forward(x, shift, scale, 1, inp.T, inp.D, 1e-6, s, tmp, y, mean, rstd,
                                        lnmod.LNMOD_BF16) == lnmod.LNMOD_OK
     torch.cuda.synchronize()
     y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, B=1, S=inp.T)
@@ -509,7 +588,7 @@ def test_unfused_comparator_and_copy_match():
     assert np.abs(got - y64).max() <= 2e-2 + 2.0 ** -7 * np.abs(y64).max()
     check_stats(mean, rstd, mean64, rstd64)
     dst = torch.zeros_like(x)
-    assert lnmod.lnmod_copy(x, dst, x.numel() * 2, s) == lnmod.LNMOD_OK
+    assert lnmod_tools.lnmod_copy(x, dst, x.numel() * 2, s) == lnmod.LNMOD_OK
     torch.cuda.synchronize()
     assert torch.equal(dst, x)
 
@@ -571,19 +650,32 @@ def test_stream_probes_move_what_they_say():
     n = 3 * 1024 * 1024 + 4096 + 48                    # bytes: whole pieces plus a tail that is left out
     g = torch.Generator(device="cuda")
     g.manual_seed(11)
-    a = torch.randint(0, 2 ** 31 - 1, (n // 4,), generator=g, device="cuda", dtype=torch.int32)
-    b = torch.randint(0, 2 ** 31 - 1, (n // 4,), generator=g, device="cuda", dtype=torch.int32)
-    c = torch.full((n // 4,), -7, device="cuda", dtype=torch.int32)
-    assert lnmod.lnmod_stream_probe(a, b, c, n, lnmod.LNMOD_PROBE_ADD, st) == 0
-    torch.cuda.synchronize()
-    whole = (n // 4096) * 4096 // 4                     # 4 KB pieces
-    assert torch.equal(c[:whole], a[:whole] + b[:whole])            # int32 wraps like the 32-bit lanes
-    assert bool((c[whole:] == -7).all())
+    ins = [torch.randint(0, 2 ** 29, (n // 4,), generator=g, device="cuda", dtype=torch.int32) for _ in range(4)]
+    outs = [torch.full((n // 4,), -7, device="cuda", dtype=torch.int32) for _ in range(3)]
+    probe = lnmod_tools.lnmod_stream_probe
+    for nr, nw in lnmod_tools.PROBE_MIXTURES:
+        if nr == 0 or nw == 0:
+            continue
+        for launch in ((0, 0, 0), (64, 2, 8), (300, 8, 1)):
+            for o in outs:
+                o.fill_(-7)
+            assert probe(ins[:nr], outs[:nw], n, st, launch=launch) == 0
+            torch.cuda.synchronize()
+            piece = (launch[2] or 4) * 1024                 # bytes one wave moves per step
+            whole = (n // piece) * piece // 4
+            want = sum(ins[1:nr], ins[0]).view(-1, 4)[: whole // 4]
+            for j in range(nw):
+                got = outs[j][:whole].view(-1, 4)
+                assert torch.equal(got[:, 1:], want[:, 1:]) and torch.equal(got[:, 0], want[:, 0] + j), (nr, nw, launch, j)
+                assert bool((outs[j][whole:] == -7).all())
+            for o in outs[nw:]:
+                assert bool((o == -7).all())
+    c = outs[0]
     c.fill_(-7)
-    assert lnmod.lnmod_stream_probe(a, None, c, n, lnmod.LNMOD_PROBE_READ, st) == 0
+    assert probe(ins[:1], [c], n, st, writes=0) == 0
     torch.cuda.synchronize()
     assert bool((c == -7).all())                        # the read probe stores nothing
-    assert lnmod.lnmod_stream_probe(None, None, c, n, lnmod.LNMOD_PROBE_WRITE, st) == 0
+    assert probe([], [c], n, st) == 0
     torch.cuda.synchronize()
     whole8 = (n // 8192) * 8192 // 4                    # 8 KB pieces
     w = c[:whole8].view(-1, 4)

@@ -1,0 +1,98 @@
+"""GPU checks of the measurement library's shaped calls (include/lnmod_tools.h): results under a
+given launch shape still match the float64 oracle, a combination that was not compiled fails
+without running anything, and shape = NULL is the operator library's launch bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_17923_amd import lnmod, lnmod_tools, synth
+from parity_util import check_f32_tensor, check_io_tensor, check_stats, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def shaped_forward(shape, x, shift, scale, cu, n, s_or_t, D, mod=0):
+    T = x.shape[0]
+    y = torch.empty_like(x)
+    mean = torch.empty(T, dtype=torch.float32, device=x.device)
+    rstd = torch.empty(T, dtype=torch.float32, device=x.device)
+    st = lnmod_tools.lnmod_forward_shaped(shape, x, shift, scale, cu, n, s_or_t, D, 1e-6,
+                                          torch.cuda.current_stream().cuda_stream, y, mean, rstd, lnmod.LNMOD_BF16, mod)
+    return st, y, mean, rstd
+
+
+def shaped_backward(shape, dy, x, scale, cu, n, s_or_t, D, mean, rstd):
+    T = x.shape[0]
+    dx = torch.empty_like(x)
+    dsh = torch.empty(n, D, dtype=torch.float32, device=x.device)
+    dsc = torch.empty(n, D, dtype=torch.float32, device=x.device)
+    need = lnmod_tools.lnmod_backward_workspace_bytes_shaped(shape, n, T, D, 0)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    st = lnmod_tools.lnmod_backward_shaped(shape, dy, x, scale, cu, n, s_or_t, D, 1e-6,
+                                           torch.cuda.current_stream().cuda_stream, mean, rstd, dx, dsh, dsc, ws,
+                                           ws.numel(), lnmod.LNMOD_BF16, 0)
+    return st, dx, dsh, dsc
+
+
+def run_shaped(inp, fwd, bwd, rc, label):
+    """Forward with shape `fwd`, backward with saved statistics (`bwd`) and without (`rc`)."""
+    print("shaped case", label, fwd, bwd, rc, flush=True)
+    w = inp.workload
+    T, D = inp.T, inp.D
+    x, dy = to_device(inp.x, "bf16"), to_device(inp.dy, "bf16")
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    cu64 = inp.cu_seqlens.astype(np.int64)
+    cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda() if w.varlen else None
+    n, s_or_t = (inp.B, T) if w.varlen else (inp.B, inp.S)
+    st, y, mean, rstd = shaped_forward(fwd, x, shift, scale, cu, n, s_or_t, D)
+    assert st == 0, lnmod.lnmod_status_string(st)
+    torch.cuda.synchronize()
+    y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, w.eps, cu=cu64)
+    check_io_tensor("y", y, y64, "bf16")
+    check_stats(mean, rstd, mean64, rstd64)
+    dx64, dsh64, dsc64 = oracle.backward(inp.dy, inp.x, inp.scale, w.eps, cu=cu64)
+    for shape, stats in ((bwd, (mean, rstd)), (rc, (None, None))):
+        st, dx, dsh, dsc = shaped_backward(shape, dy, x, scale, cu, n, s_or_t, D, *stats)
+        assert st == 0, lnmod.lnmod_status_string(st)
+        torch.cuda.synchronize()
+        check_io_tensor("dx", dx, dx64, "bf16")
+        check_f32_tensor("dshift", dsh, dsh64)
+        check_f32_tensor("dscale", dsc, dsc64)
+
+
+# shapes that are compiled for bf16 rows of 5120 features (entries of the tables at other widths)
+@pytest.mark.parametrize("fwd,bwd,rc", [((4, 3, 1, 2), (5, 2, 2, 1), (8, 2, 2, 1)),
+                                         ((6, 3, 1, 1), (6, 2, 1, 3), (4, 3, 2, 4)),
+                                         ((5, 2, 1, 3), (8, 2, 1, 2), (4, 3, 1, 1))])
+def test_given_shapes_match_the_oracle(fwd, bwd, rc):
+    run_shaped(synth.make_inputs(2, S=2053), fwd, bwd, rc, "one sample")
+    lengths = (37, 0, 1560, 5, 819, 1, 0, 0, 300, 64, 2, 777, 0)
+    run_shaped(synth.make_inputs(4, lengths=lengths), fwd, bwd, rc, "varlen")
+
+
+def test_uncompiled_shape_fails_and_no_shape_is_the_operator_librarys_launch():
+    inp = synth.make_inputs(2, S=1000)
+    assert inp.D == 5120
+    x, dy = to_device(inp.x, "bf16"), to_device(inp.dy, "bf16")
+    shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+    y0, mean0, rstd0 = lnmod.forward(x.view(1, 1000, inp.D), shift, scale)
+    dx0, dsh0, dsc0 = lnmod.backward(dy.view(1, 1000, inp.D), x.view(1, 1000, inp.D), scale, mean0, rstd0)
+    torch.cuda.synchronize()
+    st, _, _, _ = shaped_forward((7, 2, 1, 1), x, shift, scale, None, 1, 1000, inp.D)       # no 7-wave kernel
+    assert st == lnmod.LNMOD_ELAUNCH
+    st, _, _, _ = shaped_forward((2, 2, 1, 4), x, shift, scale, None, 1, 1000, inp.D)       # 256 of 640 chunks
+    assert st == lnmod.LNMOD_ELAUNCH
+    st, y1, mean1, rstd1 = shaped_forward(None, x, shift, scale, None, 1, 1000, inp.D)
+    assert st == 0
+    st, dx1, dsh1, dsc1 = shaped_backward(None, dy, x, scale, None, 1, 1000, inp.D, mean1, rstd1)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert torch.equal(y0.view_as(y1), y1) and torch.equal(mean0.view_as(mean1), mean1) and torch.equal(rstd0.view_as(rstd1), rstd1)
+    assert torch.equal(dx0.view_as(dx1), dx1) and torch.equal(dsh0, dsh1) and torch.equal(dsc0, dsc1)
+    # the table's own entry given explicitly is the same launch again
+    st, tab = lnmod_tools.lnmod_table_shape(lnmod_tools.LNMOD_FAMILY_FORWARD, inp.D, 0, 1000)
+    assert st == 0
+    st, y2, _, _ = shaped_forward(tab, x, shift, scale, None, 1, 1000, inp.D)
+    torch.cuda.synchronize()
+    assert st == 0 and torch.equal(y1, y2)

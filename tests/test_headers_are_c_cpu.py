@@ -1,5 +1,5 @@
 """The public headers are C: a C99 translation unit that includes all three compiles without
-warnings, links against the built library and calls its host-side entry points (no GPU needed)."""
+warnings, links against the built libraries and calls its host-side entry points (no GPU needed)."""
 import os
 import shutil
 import subprocess
@@ -21,7 +21,7 @@ def test_c_program_compiles_links_and_runs(tmp_path):
     exe = str(tmp_path / "c_abi_check")
     libdir = os.path.dirname(lnmod.LIBRARY)
     build = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
-                            os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-l:liblnmod.so",
+                            os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", exe, "-L", libdir, "-l:liblnmod.so", "-l:liblnmod_tools.so",
                             "-Wl,-rpath," + libdir], capture_output=True, text=True)
     assert build.returncode == 0, build.stdout + build.stderr
     run = subprocess.run([exe], capture_output=True, text=True, timeout=60)
