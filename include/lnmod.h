@@ -123,6 +123,27 @@ int lnmod_backward_varlen(const void* dy, const void* x, const void* shift, cons
                           void* workspace, size_t workspace_bytes, int dtype);
 
 /*
+ * lnmod_backward for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as lnmod_backward (bit for bit: the same kernels and launch plan) without
+ * `workspace` / `workspace_bytes`: the per-block partial sums go to a static device array of
+ * LNMOD_STATIC_WORKSPACE_BYTES inside the library (one per GPU, held from the time the library's
+ * code is loaded on that GPU until the process ends).  The call allocates nothing, frees nothing
+ * and never synchronises.  A LNMOD_PER_SAMPLE problem whose partial sums need more than that
+ * (about 1600 slots of 2*D floats at D = 5120) is refused with LNMOD_EWORKSPACE before anything is
+ * enqueued; LNMOD_PER_TOKEN needs no workspace and is never refused for it.  Every call on a GPU
+ * uses that GPU's one array: calls that may overlap in time on the same GPU (different streams,
+ * different host threads) race on it and must be serialised by the caller; calls on one stream
+ * are ordered and safe.  The array needs no clearing between calls (every slot that is read has
+ * been written by the same call).
+ */
+#define LNMOD_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int lnmod_backward_static(const void* dy, const void* x, const void* shift, const void* scale,
+                          int64_t B, int64_t S, int64_t D, float eps, void* stream,
+                          const float* mean, const float* rstd,
+                          void* dx, void* dshift, void* dscale, int dtype, int mod);
+
+/*
  * Bytes of device workspace the backward needs for its per-block partial sums of
  * dshift/dscale (Sec. 3.3: per-feature accumulation down the sequence; the partials of the
  * blocks are combined by a second, fixed-order kernel).  0 for LNMOD_PER_TOKEN and for invalid

@@ -21,7 +21,7 @@ TOOLS_LIBRARY = os.path.join(HERE, "liblnmod_tools.so")
 
 KERNEL_SOURCES = ["lnmod_fwd.hip", "lnmod_bwd.hip", "lnmod_gated_fwd.hip", "lnmod_gated_bwd.hip",
                   "lnmod_qknorm.hip"]
-LIBRARY_SOURCES = KERNEL_SOURCES + ["lnmod_api.cpp", "lnmod_sched.cpp"]
+LIBRARY_SOURCES = KERNEL_SOURCES + ["lnmod_static_ws.hip", "lnmod_api.cpp", "lnmod_sched.cpp"]
 TOOLS_SOURCES = KERNEL_SOURCES + ["lnmod_misc.hip", "lnmod_tools_api.cpp"]
 SOURCES = LIBRARY_SOURCES + [s for s in TOOLS_SOURCES if s not in LIBRARY_SOURCES]
 HEADERS = [os.path.join(CSRC, "lnmod_kernels.hpp"), os.path.join(CSRC, "lnmod_launch.hpp"),

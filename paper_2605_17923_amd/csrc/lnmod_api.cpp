@@ -2,6 +2,8 @@
 // The library keeps no mutable state: a call's result depends on its arguments alone.
 #include "lnmod_api_impl.hpp"
 
+static_assert(LNMOD_STATIC_WORKSPACE_BYTES == lnmod::kStaticWorkspaceBytes, "header and library disagree");
+
 namespace {
 
 using lnmod::Problem;
@@ -79,6 +81,39 @@ int lnmod_backward_varlen(const void* dy, const void* x, const void* shift, cons
     (void)shift;
     return backward_impl(dy, x, scale, cu_seqlens, true, nseg, 0, T, D, eps, stream, mean, rstd,
                          dx, dshift, dscale, workspace, workspace_size, dtype, LNMOD_PER_SAMPLE);
+}
+
+int lnmod_backward_static(const void* dy, const void* x, const void* shift, const void* scale,
+                          int64_t B, int64_t S, int64_t D, float eps, void* stream,
+                          const float* mean, const float* rstd, void* dx, void* dshift,
+                          void* dscale, int dtype, int mod) {
+    (void)shift;
+    const int64_t T = total_tokens(B, S);
+    if (T < 0) return LNMOD_EINVAL;
+    if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
+    const int st = check_shape(B, S, D, eps, dtype, T);
+    if (st != LNMOD_OK) return st;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    if (mod == LNMOD_PER_SAMPLE && T > 0 && B > 0) {
+        // the slots of exactly this call's plan (element type and whether the statistics are
+        // recomputed are known here), not the query's upper bound over all plans
+        if ((mean == nullptr) != (rstd == nullptr)) return LNMOD_EINVAL;
+        const lnmod::RowPlan pl = lnmod::bwd_plan(T, B, D, dtype, mean == nullptr);
+        const size_t need = static_cast<size_t>(lnmod::bwd_slots(pl, B)) * 2u * static_cast<size_t>(D) * sizeof(float);
+        if (need > lnmod::kStaticWorkspaceBytes) return LNMOD_EWORKSPACE;
+        // every other argument is checked before the first HIP call
+        if (!dy || !x || !scale || !dx || !dshift || !dscale) return LNMOD_EINVAL;
+        if (!aligned16(dy) || !aligned16(x) || !aligned16(scale) || !aligned16(dx) ||
+            !aligned16(dshift) || !aligned16(dscale))
+            return LNMOD_EALIGN;
+        float* p = nullptr;
+        if (lnmod::static_workspace(&p) != hipSuccess) return LNMOD_ELAUNCH;
+        ws = p;
+        ws_bytes = lnmod::kStaticWorkspaceBytes;
+    }
+    return backward_impl(dy, x, scale, nullptr, false, B, S, T, D, eps, stream, mean, rstd, dx,
+                         dshift, dscale, ws, ws_bytes, dtype, mod, nullptr, /*exact_workspace=*/true);
 }
 
 size_t lnmod_backward_workspace_bytes(int64_t B_or_nseg, int64_t total, int64_t D, int mod) {

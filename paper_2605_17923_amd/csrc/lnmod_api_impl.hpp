@@ -69,7 +69,7 @@ inline int backward_impl(const void* dy, const void* x, const void* scale, const
                          int64_t nseg, int64_t S, int64_t T, int64_t D, float eps, void* stream,
                          const float* mean, const float* rstd, void* dx, void* dshift, void* dscale,
                          void* workspace, size_t workspace_size, int dtype, int mod,
-                         const Shape* force = nullptr) {
+                         const Shape* force = nullptr, bool exact_workspace = false) {
     if (mod != LNMOD_PER_SAMPLE && mod != LNMOD_PER_TOKEN) return LNMOD_EINVAL;
     const int st = check_shape(nseg, varlen ? T : S, D, eps, dtype, T);
     if (st != LNMOD_OK) return st;
@@ -95,7 +95,13 @@ inline int backward_impl(const void* dy, const void* x, const void* scale, const
     if (mod == LNMOD_PER_TOKEN) {
         e = launch_bwd_tok(p, dy, x, scale, mean, rstd, dx, dshift, dscale, hs);
     } else {
-        if (!workspace || workspace_size < workspace_bytes(nseg, T, D, force)) return LNMOD_EWORKSPACE;
+        // exact_workspace: the caller has sized the workspace for this very plan (element type,
+        // statistics recomputed or not) instead of the query's bound over all plans
+        const size_t need =
+            exact_workspace ? static_cast<size_t>(bwd_slots(bwd_plan(T, nseg, D, dtype, mean == nullptr, force), nseg)) *
+                                  2u * static_cast<size_t>(D) * sizeof(float)
+                            : workspace_bytes(nseg, T, D, force);
+        if (!workspace || workspace_size < need) return LNMOD_EWORKSPACE;
         if (!aligned16(workspace)) return LNMOD_EALIGN;
         e = launch_bwd_seg(p, dy, x, scale, mean, rstd, dx, static_cast<float*>(dshift),
                                   static_cast<float*>(dscale), static_cast<float*>(workspace), hs);

@@ -343,6 +343,12 @@ inline ReduceShape reduce_shape(int64_t nseg, int nsum, int64_t D, int64_t clust
     return sh;
 }
 
+// The backward entry point that allocates nothing keeps its partial-sum slots in a static device
+// array of this size (per GPU); static_workspace() returns that array's address on the current
+// device.
+constexpr size_t kStaticWorkspaceBytes = size_t(64) << 20;
+hipError_t static_workspace(float** ptr);
+
 // Text naming the kernel instantiations and grids that a call with these arguments launches.
 int describe_fwd(const Problem& p, bool per_token, char* buf, size_t n);
 int describe_bwd(const Problem& p, bool per_token, bool recompute, char* buf, size_t n);

@@ -19,8 +19,10 @@ LNMOD_PER_SAMPLE, LNMOD_PER_TOKEN = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(_HERE, "liblnmod.so")
 
+LNMOD_STATIC_WORKSPACE_BYTES = 64 << 20
+
 EXPORTS = ("lnmod_forward", "lnmod_backward", "lnmod_forward_varlen", "lnmod_backward_varlen",
-           "lnmod_backward_workspace_bytes", "lnmod_status_string", "lnmod_gated_forward",
+           "lnmod_backward_static", "lnmod_backward_workspace_bytes", "lnmod_status_string", "lnmod_gated_forward",
            "lnmod_gated_backward", "lnmod_gated_backward_workspace_bytes", "lnmod_qknorm_forward",
            "lnmod_qknorm_backward", "lnmod_qknorm_backward_workspace_bytes")
 
@@ -49,6 +51,9 @@ def library() -> ctypes.CDLL:
     lib.lnmod_backward.restype = cint
     lib.lnmod_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, vp, vp, vp, vp, vp, vp,
                                    vp, sz, cint, cint]
+    lib.lnmod_backward_static.restype = cint
+    lib.lnmod_backward_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, vp, vp, vp, vp, vp, vp,
+                                          cint, cint]
     lib.lnmod_forward_varlen.restype = cint
     lib.lnmod_forward_varlen.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, vp, vp, vp, vp, cint]
     lib.lnmod_backward_varlen.restype = cint
@@ -106,6 +111,13 @@ def lnmod_backward(dy, x, shift, scale, B, S, D, eps, stream, mean, rstd, dx, ds
     return library().lnmod_backward(_p(dy), _p(x), _p(shift), _p(scale), B, S, D, eps, stream,
                                     _p(mean), _p(rstd), _p(dx), _p(dshift), _p(dscale),
                                     _p(workspace), workspace_bytes, dtype, mod)
+
+
+def lnmod_backward_static(dy, x, shift, scale, B, S, D, eps, stream, mean, rstd, dx, dshift, dscale,
+                          dtype, mod):
+    return library().lnmod_backward_static(_p(dy), _p(x), _p(shift), _p(scale), B, S, D, eps, stream,
+                                           _p(mean), _p(rstd), _p(dx), _p(dshift), _p(dscale),
+                                           dtype, mod)
 
 
 def lnmod_forward_varlen(x, shift, scale, cu_seqlens, nseg, T, D, eps, stream, y, mean, rstd, dtype):

@@ -155,6 +155,26 @@ def test_workspace_query(lib):
     assert q(1, 10, 5120, 0) <= n
 
 
+def test_backward_static_validates_like_backward_and_refuses_what_does_not_fit(lib):
+    E = lnmod
+
+    def sb(dy=A, x=A, scale=A, B=2, S=4, D=64, eps=1e-6, mean=A, rstd=A, dx=A, dshift=A, dscale=A, dtype=0, mod=0):
+        return lnmod.lnmod_backward_static(dy, x, None, scale, B, S, D, eps, None, mean, rstd, dx, dshift, dscale,
+                                           dtype, mod)
+    assert sb(dy=None) == E.LNMOD_EINVAL and sb(dx=None) == E.LNMOD_EINVAL and sb(dscale=None) == E.LNMOD_EINVAL
+    assert sb(mean=None) == E.LNMOD_EINVAL and sb(eps=0.0) == E.LNMOD_EINVAL and sb(mod=2) == E.LNMOD_EINVAL
+    assert sb(B=-1) == E.LNMOD_EINVAL and sb(B=1 << 40, S=1 << 40) == E.LNMOD_EINVAL
+    assert sb(D=63) == E.LNMOD_EUNSUPPORTED and sb(D=8200) == E.LNMOD_EUNSUPPORTED
+    assert sb(x=A + 4) == E.LNMOD_EALIGN and sb(dshift=A + 8) == E.LNMOD_EALIGN
+    assert sb(B=0, S=0) == E.LNMOD_OK and sb(B=0, S=5) == E.LNMOD_OK
+    # the headline problem needs 256 slots of 40 KB: it fits; 3000 samples at D = 8192 do not
+    assert 256 * 2 * 5120 * 4 <= lnmod.LNMOD_STATIC_WORKSPACE_BYTES
+    assert sb(B=3000, S=40, D=8192) == E.LNMOD_EWORKSPACE
+    assert sb(B=3000, S=40, D=8192, mean=None, rstd=None) == E.LNMOD_EWORKSPACE
+    header = open(HEADER).read()
+    assert "#define LNMOD_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)" in header
+
+
 def gfwd(x=A, u=A, gate=A, shift=A, scale=A, cu=None, n=2, s=4, D=64, eps=1e-6, h=A, y=A, mean=A,
          rstd=A, dtype=0):
     return lnmod.lnmod_gated_forward(x, u, gate, shift, scale, cu, n, s, D, eps, None, h, y, mean,
