@@ -68,6 +68,12 @@ int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t 
  *   shape[1] VPL      16-byte chunks of the row each lane holds         1..6
  *   shape[2] R        rows a block works on per step                    1..2
  *   shape[3] per_cu   resident blocks per compute unit that the grid is sized for   1..16
+ *   shape[4] clusters 0: the plan's choice; 1..256: that many groups of blocks, each streaming
+ *                     through its own contiguous share of the rows (per-sample kernels only)
+ *   shape[5] interleave  0: consecutive blocks form a cluster (every cluster is spread over all
+ *                     XCDs); 1: cluster = block index modulo the cluster count, so that with 8
+ *                     clusters each cluster's blocks all sit on one XCD
+ * (a host array of 6 ints).
  * Results do not depend on the shape beyond the order of fp32 summation.  A shape whose K * VPL *
  * 64 chunks do not cover the row, or whose (K, VPL) is not compiled for the kernel family and
  * element type, fails with LNMOD_ELAUNCH and enqueues nothing; values outside the ranges above are

@@ -94,6 +94,7 @@ BwdArgs make_args(const Problem& p, const void* dy, const void* x, const void* s
     a.T = p.T;
     a.rows_per_cluster = 0;
     a.nb = 1;
+    a.interleave = 0;
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.inv_D = 1.0f / static_cast<float>(p.D);
@@ -151,7 +152,7 @@ BwdLaunch plan_bwd(int64_t T, int64_t nseg, int64_t D, int dtype, bool per_token
     const double elem = dtype == 0 ? 2.0 : 4.0;
     const double stream_us = static_cast<double>(T) * static_cast<double>(D) * 3.0 * elem / 5.8e6;
     L.pl = plan_rows_slots(T, nseg, static_cast<int64_t>(kNumCU) * L.sh.per_cu, L.sh.R, stream_us,
-                           16.0 / (3.0 * elem));
+                           16.0 / (3.0 * elem), L.sh.clusters);
     return L;
 }
 
@@ -173,6 +174,7 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
+    a.interleave = sh.interleave;
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch_seg<f32_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
     if (!ok) return hipErrorInvalidConfiguration;

@@ -23,6 +23,7 @@ FwdArgs make_args(const Problem& p, const void* x, const void* shift, const void
     a.T = p.T;
     a.rows_per_cluster = 0;
     a.nb = 1;
+    a.interleave = 0;
     a.D = static_cast<int32_t>(p.D);
     a.nchunks = static_cast<int32_t>(p.D / E);
     a.eps = p.eps;
@@ -118,7 +119,8 @@ FwdLaunch plan_fwd(const Problem& p, int mode) {
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
     L.sh = sh;
     L.pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
-                              sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1);
+                              sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1,
+                              per_segment ? sh.clusters : 0);
     return L;
 }
 
@@ -132,6 +134,7 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
     const RowPlan pl = L.pl;
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
+    a.interleave = sh.interleave;
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const bool ok = p.dtype == 0 ? dispatch<bf16_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch<f32_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);

@@ -223,6 +223,7 @@ struct FwdArgs {
     int64_t T;               // total token rows
     int64_t rows_per_cluster; // rows of the contiguous region one cluster of blocks streams through
     int32_t nb;              // blocks per cluster (per-token kernels: unused)
+    int32_t interleave;      // 1: cluster = block index modulo the cluster count (measurement only)
     int32_t D;
     int32_t nchunks;         // D / E
     float eps;
@@ -287,8 +288,13 @@ void fwd_split_kernel(const FwdArgs a) {
     for (int w = 1; w < K; ++w) my_cnt = wave == w ? cnt[w] : my_cnt;
     const float inv_my_cnt = my_cnt > 0.0f ? 1.0f / my_cnt : 0.0f;
 
-    const int64_t cluster = blockIdx.x / a.nb;
-    const int64_t member = blockIdx.x - cluster * a.nb;
+    int64_t cluster = blockIdx.x / a.nb;
+    int64_t member = blockIdx.x - cluster * a.nb;
+    if (a.interleave) {
+        const int64_t nclusters = gridDim.x / a.nb;
+        member = blockIdx.x / nclusters;
+        cluster = blockIdx.x - member * nclusters;
+    }
     int64_t r0 = cluster * a.rows_per_cluster;
     int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
@@ -501,6 +507,7 @@ struct BwdArgs {
     int64_t T;
     int64_t rows_per_cluster;
     int32_t nb;              // blocks per cluster
+    int32_t interleave;      // 1: cluster = block index modulo the cluster count (measurement only)
     int32_t D;
     int32_t nchunks;
     float inv_D;
@@ -558,8 +565,13 @@ void bwd_seg_kernel(const BwdArgs a) {
         inv_own = own > 0 ? 1.0f / static_cast<float>(own * E) : 0.0f;
     }
 
-    const int64_t cluster = blockIdx.x / a.nb;
-    const int64_t member = blockIdx.x - cluster * a.nb;
+    int64_t cluster = blockIdx.x / a.nb;
+    int64_t member = blockIdx.x - cluster * a.nb;
+    if (a.interleave) {
+        const int64_t nclusters = gridDim.x / a.nb;
+        member = blockIdx.x / nclusters;
+        cluster = blockIdx.x - member * nclusters;
+    }
     int64_t r0 = cluster * a.rows_per_cluster;
     int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;

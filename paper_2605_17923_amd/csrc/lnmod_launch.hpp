@@ -17,6 +17,11 @@ struct Shape {
     int VPL;
     int R;
     int per_cu;
+    // Only ever set by a shaped call of the measurement library (the tables leave them 0):
+    int clusters = 0;      // > 0: this many clusters of blocks instead of the plan's choice
+    int interleave = 0;    // 1: cluster = block index modulo the cluster count (with 8 clusters every
+                           // cluster then sits on one XCD, because consecutive blocks go to the XCDs in
+                           // turn); 0: consecutive blocks form a cluster (every cluster on all XCDs)
 };
 
 struct Problem {
@@ -101,8 +106,9 @@ inline RowPlan plan_rows(int64_t T, int64_t max_blocks, int rows_per_step) {
 // Forward with per-segment modulation rows: about `want` clusters (see pick_clusters), nb a
 // power of two.
 inline RowPlan plan_rows_clusters(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
-                                  int64_t want) {
+                                  int64_t want, int64_t forced = 0) {
     const int64_t g = grid_blocks(T, max_blocks, rows_per_step);
+    if (forced > 0) return make_plan(T, g, g / forced > 0 ? g / forced : 1);
     if (nseg <= 1 || want <= 1) return make_plan(T, g, g);
     int64_t nb = 1;
     while (nb * 2 * want <= g) nb *= 2;
@@ -131,11 +137,13 @@ inline double cluster_penalty(int64_t C) {
 // where slot_rows is what one slot costs in units of one row's traffic and stream_us the time
 // the rows take at the streaming rate.
 inline RowPlan plan_rows_slots(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
-                               double stream_us, double slot_rows) {
+                               double stream_us, double slot_rows, int64_t forced = 0) {
     if (T <= 0) return RowPlan{0, 0, 1, 1};
     const int64_t g = grid_blocks(T, max_blocks, rows_per_step);
     int64_t nb = g;
-    if (nseg > 1) {
+    if (forced > 0) {
+        nb = g / forced > 0 ? g / forced : 1;
+    } else if (nseg > 1) {
         double best = 0.0;
         for (int64_t cand = 1; cand <= g; cand *= 2) {
             int64_t C = (g + cand - 1) / cand;

@@ -66,10 +66,11 @@ def library() -> ctypes.CDLL:
 
 
 def _shape(shape):
-    """(K, VPL, R, per_cu) -> int[4], None -> NULL (the table's entry)."""
+    """(K, VPL, R, per_cu[, clusters, interleave]) -> int[6], None -> NULL (the table's entry)."""
     if shape is None:
         return None
-    return (ctypes.c_int * 4)(*[int(v) for v in shape])
+    vals = [int(v) for v in shape] + [0, 0]
+    return (ctypes.c_int * 6)(*vals[:6])
 
 
 def _ptr_array(ts):

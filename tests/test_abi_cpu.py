@@ -310,7 +310,7 @@ def sbwd(shape, dy=A, x=A, scale=A, cu=None, B=2, S=4, D=64, eps=1e-6, mean=A, r
 def test_shaped_calls_validate_the_shape_and_then_like_the_operator_calls(tools):
     E = lnmod
     for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (0, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
-                (1, 1, 1, 0), (1, 1, 1, 17)):
+                (1, 1, 1, 0), (1, 1, 1, 17), (1, 1, 1, 4, -1, 0), (1, 1, 1, 4, 257, 0), (1, 1, 1, 4, 8, 2)):
         assert sfwd(bad) == E.LNMOD_EINVAL, bad
         assert sbwd(bad) == E.LNMOD_EINVAL, bad
         assert T.lnmod_backward_workspace_bytes_shaped(bad, 1, 100, 64, 0) == 0
@@ -370,4 +370,6 @@ def test_describe_launch_names_the_kernels_of_the_headline_workload(tools):
     assert d(True, None, 2, 32760, False, 5120, 0, 1).startswith("bwd_seg_kernel<bf16_io, 2, 5, 1, true, true, true, false>")
     assert "reduce" not in d(True, None, 2, 32760, False, 5120, 0, 1)
     assert d(False, (4, 3, 1, 2), 1, 75600, False, 5120, 0, 0).startswith("fwd_split_kernel<bf16_io, 3, 4, 1, false, 0, true> grid=512")
+    assert d(False, (5, 2, 2, 1, 8, 1), 1, 75600, False, 5120, 0, 0).endswith("grid=256 block=320 clusters=8")
+    assert d(True, (4, 3, 2, 1, 8, 1), 1, 75600, False, 5120, 0, 0).endswith("slots=256")
     assert d(False, None, 1, 0, False, 5120, 0, 0) == "" and d(False, None, 1, 10, False, 5121, 0, 0) == ""

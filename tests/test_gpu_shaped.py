@@ -71,6 +71,16 @@ def test_given_shapes_match_the_oracle(fwd, bwd, rc):
     run_shaped(synth.make_inputs(4, lengths=lengths), fwd, bwd, rc, "varlen")
 
 
+@pytest.mark.parametrize("clusters,interleave", [(8, 1), (8, 0), (3, 1), (2, 0), (64, 1)])
+def test_given_cluster_counts_and_block_interleaving_match_the_oracle(clusters, interleave):
+    # clusters of blocks with their own share of the rows, either made of consecutive blocks or of every
+    # clusters-th block (all of one cluster on one XCD when there are 8): same results, other slots
+    fwd, bwd, rc = (5, 2, 2, 1, clusters, interleave), (4, 3, 2, 1, clusters, interleave), (4, 3, 1, 2, clusters, interleave)
+    run_shaped(synth.make_inputs(2, S=2053), fwd, bwd, rc, "one sample, %d clusters" % clusters)
+    lengths = (37, 0, 1560, 5, 819, 1, 0, 0, 300, 64, 2, 777, 0)
+    run_shaped(synth.make_inputs(4, lengths=lengths), fwd, bwd, rc, "varlen, %d clusters" % clusters)
+
+
 def test_uncompiled_shape_fails_and_no_shape_is_the_operator_librarys_launch():
     inp = synth.make_inputs(2, S=1000)
     assert inp.D == 5120
