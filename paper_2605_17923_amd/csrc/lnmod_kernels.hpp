@@ -886,6 +886,7 @@ struct ReduceArgs {
 };
 
 constexpr int kReduceWaves = 16;     // most waves a reduce block may have
+constexpr int kReduceBatch = 16;     // slot loads a wave keeps in flight
 
 template <int V> struct FVec { typedef float type __attribute__((ext_vector_type(V))); };
 template <> struct FVec<1> { typedef float type; };
@@ -914,16 +915,17 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const R
             const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
             const float* base = a.ws + static_cast<int64_t>(which) * a.D + d;
             const int64_t pitch = static_cast<int64_t>(a.nsum) * a.D;
-            // four slots requested before the first is added; the additions keep slot order
-            for (int64_t sl = s_lo + wave; sl < s_hi; sl += 4 * W) {
-                vec v[4];
+            // kReduceBatch slots requested before the first is added (the chain of dependent round
+            // trips, not the bytes, is what this kernel's time consists of); the additions keep slot order
+            for (int64_t sl = s_lo + wave; sl < s_hi; sl += kReduceBatch * W) {
+                vec v[kReduceBatch];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kReduceBatch; ++u) {
                     const int64_t su = sl + static_cast<int64_t>(u) * W;
                     v[u] = su < s_hi ? *reinterpret_cast<const vec*>(base + su * pitch) : vec(0.0f);
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc += v[u];
+                for (int u = 0; u < kReduceBatch; ++u) acc += v[u];
             }
         }
         if (W > 1) {
