@@ -289,13 +289,15 @@ def main():
     print(json.dumps(out))
 
 
-def condition(torch, stream, step, group=8, tol=0.01, min_groups=3, cap_ms=300.0):
+def condition(torch, stream, step, group=8, tol=0.01, min_ms=100.0, cap_ms=300.0):
     """Untimed, bounded conditioning before the warm-up and the timed steps.  A process that has
-    just started finds the GPU at idle clocks; the first steps then run 10-40 % slow and speed up
-    over some tens of milliseconds, which `warmup` steps of 0.6 ms do not cover.  The step is run
-    in groups of `group`; the phase ends when a group's mean step time is no longer more than
-    `tol` below the previous group's (and at least `min_groups` groups have run), or after `cap_ms`
-    of GPU time.  Nothing measured here enters the reported figures."""
+    just started finds the GPU at idle clocks: the first steps run up to 40 % slow, speed up over
+    some tens of milliseconds, sit on a plateau about 5 % above the final rate for another ten and
+    only then reach it (per-step kernel times of such a run are in profiles/), which `warmup`
+    steps of 0.6 ms do not cover.  The step is run in groups of `group` for at least `min_ms` of
+    GPU time; after that the phase ends as soon as a group's mean step time is no longer more than
+    `tol` below the previous group's, or after `cap_ms`.  Nothing measured here enters the
+    reported figures; what was done is reported beside them."""
     means = []
     spent = 0.0
     reason = "cap"
@@ -309,7 +311,7 @@ def condition(torch, stream, step, group=8, tol=0.01, min_groups=3, cap_ms=300.0
         ms = a.elapsed_time(b)
         spent += ms
         means.append(ms / group)
-        if len(means) >= min_groups and means[-1] >= means[-2] * (1.0 - tol):
+        if spent >= min_ms and len(means) >= 2 and means[-1] >= means[-2] * (1.0 - tol):
             reason = "settled"
             break
     return {"steps": group * len(means), "gpu_ms": round(spent, 2), "ended": reason,

@@ -67,6 +67,10 @@ bool dispatch(const FwdArgs& a, int VPL, int K, int R, int64_t blocks, hipStream
                 case 203: go<Tag, 2, 3, MODE>(a, R, blocks, st); return true;
                 case 206: go<Tag, 2, 6, MODE>(a, R, blocks, st); return true;
                 case 208: go<Tag, 2, 8, MODE>(a, R, blocks, st); return true;
+                case 502:                                    // compiled for one row per step only
+                    if (R != 1) return false;
+                    go_r<Tag, 5, 2, 1, MODE>(a, blocks, st);
+                    return true;
                 default: break;
             }
         } else {                                         // shape table

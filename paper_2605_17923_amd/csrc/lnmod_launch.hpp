@@ -283,7 +283,7 @@ inline bool covers(const Shape& s, int nchunks) { return s.K * s.VPL * 64 >= nch
 
 // Per-token modulation (three input streams forward; three in, three out backward).  bf16: a table
 // per 512 features like the ones above, from the same sweep over the (K, VPL) these kernels are
-// compiled for (one wave alone, or two chunks per lane on 2 to 8 waves).  Here too neighbours do
+// compiled for (one wave alone, or two chunks per lane on 2 to 8 waves, or five chunks per lane on two waves).  Here too neighbours do
 // not share winners: D = 2560 forward takes 526 us with {3,2,2,4} and 858 us with the {3,2,1,2}
 // that is best at D = 3072.  fp32: tables of the same kind (four chunks per lane once a row is
 // shared, up to six on a single wave).
@@ -293,8 +293,11 @@ inline Shape tok_fwd_shape(int nchunks, int dtype) {
             {1, 1, 2, 8},
             {1, 1, 2, 8}, {1, 2, 2, 4}, {1, 3, 2, 4}, {2, 2, 1, 4},
             {3, 2, 2, 4}, {3, 2, 1, 2}, {4, 2, 2, 3}, {4, 2, 1, 2},
-            {5, 2, 1, 3}, {5, 2, 1, 2}, {8, 2, 1, 2}, {6, 2, 2, 2},
+            {5, 2, 1, 3}, {2, 5, 1, 2}, {8, 2, 1, 2}, {6, 2, 2, 2},
             {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 2}, {8, 2, 1, 1}};
+        // D = 4616 ... 5120: two waves with five chunks per lane (one wave per SIMD, 5 KB runs per wave and
+        // stream, half as many waves at the barrier) take 452 us on 65 520 x 5120 where five waves with two
+        // chunks take 476; the same split gained nothing in the per-token backward (750 against 730 us)
         return table_entry(tab, nchunks, dtype);
     }
     static const Shape tab32[17] = {

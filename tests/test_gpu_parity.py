@@ -176,8 +176,8 @@ def test_hidden_sizes(dtype, D):
     run_case(synth.make_inputs(0, B=3, S=45, D=D, dtype=dtype), label="D=%d %s" % (D, dtype))
 
 
-@pytest.mark.parametrize("dtype,D", [("bf16", 1536), ("bf16", 520), ("bf16", 8192), ("f32", 1536),
-                                     ("f32", 100), ("f32", 6144)])
+@pytest.mark.parametrize("dtype,D", [("bf16", 1536), ("bf16", 520), ("bf16", 8192), ("bf16", 4616), ("bf16", 4864),
+                                     ("bf16", 5112), ("bf16", 5120), ("f32", 1536), ("f32", 100), ("f32", 6144)])
 def test_hidden_sizes_per_token(dtype, D):
     run_case(synth.make_inputs(3, B=2, S=67, D=D, dtype=dtype), label="per-token D=%d %s" % (D, dtype))
 
