@@ -886,7 +886,7 @@ struct ReduceArgs {
 };
 
 constexpr int kReduceWaves = 16;     // most waves a reduce block may have
-constexpr int kReduceBatch = 16;     // slot loads a wave keeps in flight
+constexpr int kReduceFloats = 16;    // floats per lane a wave keeps in flight: 16 / V slot loads
 
 template <int V> struct FVec { typedef float type __attribute__((ext_vector_type(V))); };
 template <> struct FVec<1> { typedef float type; };
@@ -897,6 +897,7 @@ template <> struct FVec<1> { typedef float type; };
 template <int V>
 __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const ReduceArgs a) {
     using vec = typename FVec<V>::type;
+    constexpr int kReduceBatch = kReduceFloats / V;
     __shared__ vec red[kReduceWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;

@@ -1,0 +1,55 @@
+"""The kernels of the measured workloads keep everything in registers: hipcc's resource report for
+the forward and backward translation units must show no scratch (spilled registers) for the launch
+shapes the tables give at the two model widths, nor for any form of the second pass.  A spill costs
+HBM traffic that no parity test notices.  (Known and left alone: the fp32 backward at D = 5120 spills
+three registers per lane at the three waves per SIMD its launch shape was measured with.)  Needs only
+hipcc (cross-compiles without a GPU)."""
+import os
+import re
+import shutil
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+from paper_2605_17923_amd import build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# template arguments as c++filt prints them: <io, VPL, K, R, EXACT, ...>
+MUST_NOT_SPILL = [
+    r"fwd_split_kernel<lnmod::bf16_io, 2, 5, 2, true, 0, true>",          # workloads [2], [4] forward
+    r"fwd_split_kernel<lnmod::bf16_io, 3, 1, 2, true, 0, true>",          # workload [1] forward
+    r"fwd_split_kernel<lnmod::bf16_io, 5, 2, 1, true, 1, true>",          # workload [3] forward (per token)
+    r"fwd_split_kernel<lnmod::f32_io, 4, 5, 1, true, 0, true>",           # fp32 I/O, D = 5120
+    r"bwd_seg_kernel<lnmod::bf16_io, 3, 4, 2, false, false, true, false>",  # workloads [2], [4] backward
+    r"bwd_seg_kernel<lnmod::bf16_io, 3, 4, 1, false, false, true, true>",   # the same without saved statistics
+    r"bwd_seg_kernel<lnmod::bf16_io, 1, 3, 1, true, false, true, false>",   # D = 1536 backward
+    r"bwd_seg_kernel<lnmod::bf16_io, 2, 5, 1, true, true, true, false>",    # workload [3] backward (per token)
+    r"bwd_reduce_kernel<1>", r"bwd_reduce_kernel<2>", r"bwd_reduce_kernel<4>",
+]
+
+
+def _report(src, tmp):
+    cmd = [build._hipcc()] + build.HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-c",
+                                                   os.path.join(build.CSRC, src), "-o", os.path.join(tmp, src + ".o")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    return res.stderr
+
+
+def test_measured_kernels_use_no_scratch(tmp_path):
+    if shutil.which(build._hipcc()) is None and not os.path.exists(build._hipcc()):
+        pytest.skip("hipcc not found")
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        text = "\n".join(pool.map(lambda s: _report(s, str(tmp_path)), ["lnmod_fwd.hip", "lnmod_bwd.hip"]))
+    names = re.findall(r"Function Name: (\S+)", text)
+    scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", text)]
+    assert len(names) == len(scratch) and len(names) > 100
+    plain = subprocess.run(["c++filt"], input="\n".join(names), capture_output=True, text=True, check=True).stdout.splitlines()
+    usage = dict(zip(plain, scratch))
+    for pattern in MUST_NOT_SPILL:
+        hits = [(k, v) for k, v in usage.items() if pattern in k]
+        assert hits, "no kernel matches " + pattern
+        for k, v in hits:
+            assert v == 0, "%s spills %d bytes per lane" % (k, v)
