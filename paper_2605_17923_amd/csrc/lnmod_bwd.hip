@@ -174,7 +174,7 @@ hipError_t launch_bwd_seg(const Problem& p, const void* dy, const void* x, const
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    a.interleave = sh.interleave;
+    a.interleave = cluster_interleave(p.force, pl);
     const bool ok = p.dtype == 0 ? dispatch_seg<bf16_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch_seg<f32_io, false>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
     if (!ok) return hipErrorInvalidConfiguration;

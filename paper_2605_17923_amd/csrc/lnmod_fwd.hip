@@ -138,7 +138,7 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
     const RowPlan pl = L.pl;
     a.rows_per_cluster = pl.rows_per_cluster;
     a.nb = pl.nb;
-    a.interleave = sh.interleave;
+    a.interleave = cluster_interleave(p.force, pl);
     if (!covers(sh, a.nchunks)) return hipErrorInvalidConfiguration;
     const bool ok = p.dtype == 0 ? dispatch<bf16_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st)
                                  : dispatch<f32_io, MODE>(a, sh.VPL, sh.K, sh.R, pl.blocks, st);
