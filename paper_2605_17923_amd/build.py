@@ -34,7 +34,11 @@ VERSION_SCRIPT = "{ global: lnmod_*; local: *; };\n"
 
 # packed-fp32 instructions are switched off on purpose (some of their forms have produced wrong
 # results on these machines); the host pass warns that it does not know the feature
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
+# -falign-loops=64: the row loops are a few KB of code that 4 to 10 waves per CU run in near lock step, and
+# where such a loop happens to start matters: with the header of the forward's loop at nine different
+# offsets (a few s_nop in front of it) workload [2] took 248.5 ... 265 us, fastest on a 64-byte boundary;
+# aligned, the forward gained 3.5 % on [2] and 2.6 % on [4] over the placement it had happened to get
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-falign-loops=64",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument", "-I", INCLUDE, "-I", CSRC]
 
