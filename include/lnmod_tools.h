@@ -73,7 +73,10 @@ int lnmod_gate_residual(const void* x, const void* u, const void* gate, int64_t 
  *   shape[5] interleave  0: consecutive blocks form a cluster (every cluster is spread over all
  *                     XCDs); 1: cluster = block index modulo the cluster count, so that with 8
  *                     clusters each cluster's blocks all sit on one XCD
- * (a host array of 6 ints).
+ *   shape[6] flat     per-sample forward only: 1 runs one loop over all rows of a block's region and
+ *                     reloads the modulation registers where the segment changes, 2 runs one loop per
+ *                     segment, 0 leaves the choice to the launcher
+ * (a host array of 7 ints).
  * Results do not depend on the shape beyond the order of fp32 summation.  A shape whose K * VPL *
  * 64 chunks do not cover the row, or whose (K, VPL) is not compiled for the kernel family and
  * element type, fails with LNMOD_ELAUNCH and enqueues nothing; values outside the ranges above are

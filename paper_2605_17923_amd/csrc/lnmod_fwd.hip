@@ -97,6 +97,30 @@ bool dispatch(const FwdArgs& a, int VPL, int K, int R, int64_t blocks, hipStream
     return false;                                        // no such instantiation
 }
 
+// Whether a forward with one modulation row per sample / segment runs one loop over all rows of a
+// block's region (kModFlat) or one loop per segment (kModSegment).  With several segments the flat
+// loop wins wherever few blocks share a CU, because a block that drains its pipeline at a segment's
+// end leaves the CU idle: bf16 rows shared by three or more waves (D >= 2560) and D = 1536 gained 1
+// to 11 % on 8 to 480 segments (D = 5120, 24 mixed segments: 514 against 530 us; 3 x 75 600 rows: 766
+// against 819; D = 1536, 24 mixed: 159 against 178, 480 x 312: 170 against 244); D = 1024 and 2048
+// lost 2 to 9 % on 96 segments and fp32 was mixed, so those keep the loop per segment.
+bool fwd_flat(const Problem& p, const Shape& table) {
+    if (p.force && p.force->flat != 0) return p.force->flat == 1;
+    if (p.nseg <= 1 || p.dtype != 0) return false;
+    return table.K >= 3 || p.D == 1536;
+}
+
+// Clusters of a flat launch: every block reloads its modulation registers once per segment of its
+// cluster's region (about 0.3 us each, the next rows being already in flight), and every further
+// window costs bandwidth, so the count is the smallest power of two that leaves a block at most 32
+// segments, between 2 and 32 (D = 5120: 2, 4, 8 clusters best on 24, 96, 480 segments; D = 1536:
+// 2, 4, 16).
+int64_t flat_clusters(int64_t nseg) {
+    int64_t c = 2;
+    while (c < 32 && nseg > 32 * c) c *= 2;
+    return c;
+}
+
 // Shape and row plan of a forward launch: what the launcher uses and what describe_fwd() reports.
 struct FwdLaunch {
     Shape sh;
@@ -110,7 +134,13 @@ FwdLaunch plan_fwd(const Problem& p, int mode) {
     L.nchunks = static_cast<int>(p.D / E);
     Shape sh = fwd_shape(L.nchunks, p.dtype);                      // the comparators' starting point
     if (mode == kModToken) sh = pick_shape(p.force, tok_fwd_shape(L.nchunks, p.dtype));
-    if (mode == kModSegment) sh = pick_shape(p.force, fwd_shape(L.nchunks, p.dtype, p.T));
+    if (mode == kModSegment || mode == kModFlat) {
+        Shape tab = fwd_shape(L.nchunks, p.dtype, p.T);
+        // D = 1536, flat: four blocks per CU at every token count (24 mixed segments, 152 880 rows:
+        // 159 us against 182 with three)
+        if (mode == kModFlat && L.nchunks == 192 && p.dtype == 0) tab.per_cu = 4;
+        sh = pick_shape(p.force, tab);
+    }
     if ((mode == kLnOnly || mode == kModOnly) && p.dtype == 0) {
         // the two kernels of the unfused comparator get the shape that makes their chain fastest at
         // the two model widths (D = 5120: 540 against 609 us, D = 1536: 528 against 559 us on 774 MB)
@@ -122,9 +152,13 @@ FwdLaunch plan_fwd(const Problem& p, int mode) {
     // bytes of x and y at 6 TB/s
     const double stream_us = static_cast<double>(p.T) * static_cast<double>(p.D) * (2.0 * E_bytes(p.dtype)) / 6.0e6;
     L.sh = sh;
-    L.pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
-                              sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1,
-                              per_segment ? sh.clusters : 0);
+    if (mode == kModFlat)
+        L.pl = plan_rows_clusters(p.T, p.nseg, static_cast<int64_t>(kNumCU) * sh.per_cu, sh.R,
+                                  flat_clusters(p.nseg), sh.clusters);
+    else
+        L.pl = plan_rows_clusters(p.T, per_segment ? p.nseg : 1, static_cast<int64_t>(kNumCU) * sh.per_cu,
+                                  sh.R, per_segment ? pick_clusters(stream_us, p.nseg) : 1,
+                                  per_segment ? sh.clusters : 0);
     return L;
 }
 
@@ -149,6 +183,8 @@ hipError_t launch_mode(const Problem& p, const void* x, const void* shift, const
 
 hipError_t launch_fwd_seg(const Problem& p, const void* x, const void* shift, const void* scale,
                           void* y, float* mean, float* rstd, hipStream_t st) {
+    if (fwd_flat(p, fwd_shape(static_cast<int>(p.D / (p.dtype == 0 ? 8 : 4)), p.dtype, p.T)))
+        return launch_mode<kModFlat>(p, x, shift, scale, y, mean, rstd, st);
     return launch_mode<kModSegment>(p, x, shift, scale, y, mean, rstd, st);
 }
 
@@ -168,7 +204,8 @@ hipError_t launch_unfused(const Problem& p, const void* x, const void* shift, co
 // Text that names the kernel instantiation and grid a forward call with these arguments launches
 // (template arguments in the order of fwd_split_kernel's parameter list).
 int describe_fwd(const Problem& p, bool per_token, char* buf, size_t n) {
-    const int mode = per_token ? kModToken : kModSegment;
+    const Shape tab = fwd_shape(static_cast<int>(p.D / (p.dtype == 0 ? 8 : 4)), p.dtype, p.T);
+    const int mode = per_token ? kModToken : fwd_flat(p, tab) ? kModFlat : kModSegment;
     const FwdLaunch L = plan_fwd(p, mode);
     const bool exact = L.nchunks == L.sh.K * L.sh.VPL * kWave;
     return std::snprintf(buf, n, "fwd_split_kernel<%s, %d, %d, %d, %s, %d, true> grid=%lld block=%d clusters=%lld",

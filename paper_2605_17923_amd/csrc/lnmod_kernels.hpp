@@ -252,8 +252,15 @@ struct FwdArgs {
 //   kModToken     y = xhat*(1+scale[n]) + shift[n], modulation rows streamed with x
 //   kLnOnly       y = xhat                      (first kernel of the unfused comparator)
 //   kModOnly      y = x*(1+scale[m]) + shift[m], no statistics (second kernel of the comparator)
+//   kModFlat      kModSegment's result for batches of several segments, with one loop over the rows
+//                 of the block's region instead of one loop per segment: a block's rows are
+//                 member*R + k*nb*R whatever segment they fall in, and when a row lies beyond the
+//                 segment whose modulation row the registers hold, the registers are reloaded on
+//                 the spot.  The software pipeline never drains at a segment boundary (the next
+//                 step's rows are already requested when the reload waits) and no step is left
+//                 partly empty at a segment's end.
 // =============================================================================================
-constexpr int kModSegment = 0, kModToken = 1, kLnOnly = 2, kModOnly = 3;
+constexpr int kModSegment = 0, kModToken = 1, kLnOnly = 2, kModOnly = 3, kModFlat = 4;
 
 template <typename Tag, int VPL, int K, int R, bool EXACT, int MODE = kModSegment, bool PF = true>
 __global__ __launch_bounds__(K* kWave)
@@ -261,7 +268,8 @@ LNMOD_OCCUPANCY(bwd_waves_per_eu(VPL, IO<Tag>::E, (MODE == kModToken ? 3 : 1) * 
 void fwd_split_kernel(const FwdArgs a) {
     using io = IO<Tag>;
     constexpr int E = io::E;
-    constexpr bool kSegMod = MODE == kModSegment || MODE == kModOnly;   // A, B per segment in registers
+    constexpr bool kFlat = MODE == kModFlat;
+    constexpr bool kSegMod = MODE == kModSegment || MODE == kModOnly || kFlat;   // A, B per segment in registers
     constexpr bool kTok = MODE == kModToken;
     constexpr bool kStats = MODE != kModOnly;
     constexpr int NS = kTok ? 3 : 1;                                     // streamed inputs per row
@@ -310,28 +318,37 @@ void fwd_split_kernel(const FwdArgs a) {
 
     while (r0 < r1) {
         int64_t m = 0, stop = r1;
-        if (kSegMod) {
+        if (kSegMod && !kFlat) {
             m = find_segment(a.seg, r0);
             stop = seg_begin(a.seg, m + 1);
             if (stop > r1) stop = r1;
             if (stop <= r0) stop = r0 + 1;      // malformed table: still make progress
         }
+        // kFlat: the segment of the block's first row; seg_end is where the rows of m end
+        int64_t seg_end = 0;
+        if (kFlat) {
+            int64_t first = r0 + member * R;
+            if (first >= r1) first = r1 - 1;
+            m = find_segment(a.seg, first);
+            seg_end = m + 1 < a.seg.nseg ? seg_begin(a.seg, m + 1) : a.T;
+        }
 
         float A[VPL][E], B[VPL][E];
-        if (kSegMod) {
+        auto load_modulation = [&](int64_t mm) {
 #pragma unroll
             for (int i = 0; i < VPL; ++i) {
                 u32x4 rsc = u32x4{0u, 0u, 0u, 0u}, rsh = u32x4{0u, 0u, 0u, 0u};
                 if (ok[i]) {
-                    rsc = load16_cached(a.scale, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
-                    rsh = load16_cached(a.shift, m * row_bytes, static_cast<uint32_t>(chunk[i]) * 16u);
+                    rsc = load16_cached(a.scale, uniform64(mm * row_bytes), static_cast<uint32_t>(chunk[i]) * 16u);
+                    rsh = load16_cached(a.shift, uniform64(mm * row_bytes), static_cast<uint32_t>(chunk[i]) * 16u);
                 }
                 io::unpack(rsc, A[i]);
                 io::unpack(rsh, B[i]);
 #pragma unroll
                 for (int e = 0; e < E; ++e) A[i][e] += 1.0f;
             }
-        }
+        };
+        if (kSegMod) load_modulation(m);
 
         // Software pipeline: the rows of the block's next step are requested before the current
         // step is computed, so a few waves per CU keep the memory system busy.
@@ -445,6 +462,14 @@ void fwd_split_kernel(const FwdArgs a) {
             for (int j = 0; j < R; ++j) {
                 const int64_t row = base + j;
                 if (row < stop) {
+                    if (kFlat && row >= seg_end) {
+                        // the row belongs to a later segment (empty ones in between are skipped); the
+                        // walk stays inside the table whatever the table holds
+                        while (m + 1 < a.seg.nseg && seg_begin(a.seg, m + 1) <= row) ++m;
+                        seg_end = m + 1 < a.seg.nseg ? seg_begin(a.seg, m + 1) : a.T;
+                        if (seg_end <= row) seg_end = row + 1;      // malformed table: still make progress
+                        load_modulation(m);
+                    }
                     if (kStats && wave == 0 && lane == 0 && a.mean != nullptr) {
                         a.mean[row] = mu[j];
                         a.rstd[row] = rs[j];

@@ -22,6 +22,9 @@ struct Shape {
     int interleave = 0;    // 1: cluster = block index modulo the cluster count (with 8 clusters every
                            // cluster then sits on one XCD, because consecutive blocks go to the XCDs in
                            // turn); 0: consecutive blocks form a cluster (every cluster on all XCDs)
+    int flat = 0;          // per-sample forward: 1 one loop over all rows of a block's region (modulation
+                           // registers reloaded where the segment changes), 2 one loop per segment,
+                           // 0 the launcher's choice
 };
 
 struct Problem {

@@ -18,8 +18,8 @@ bool read_shape(const int* shape, Shape* out, const Shape** force) {
     if (shape[0] < 1 || shape[0] > 16 || shape[1] < 1 || shape[1] > 6 || shape[2] < 1 || shape[2] > 2 ||
         shape[3] < 1 || shape[3] > 16)
         return false;
-    if (shape[4] < 0 || shape[4] > 256 || (shape[5] != 0 && shape[5] != 1)) return false;
-    *out = Shape{shape[0], shape[1], shape[2], shape[3], shape[4], shape[5]};
+    if (shape[4] < 0 || shape[4] > 256 || (shape[5] != 0 && shape[5] != 1) || shape[6] < 0 || shape[6] > 2) return false;
+    *out = Shape{shape[0], shape[1], shape[2], shape[3], shape[4], shape[5], shape[6]};
     *force = out;
     return true;
 }

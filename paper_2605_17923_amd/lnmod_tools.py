@@ -66,11 +66,11 @@ def library() -> ctypes.CDLL:
 
 
 def _shape(shape):
-    """(K, VPL, R, per_cu[, clusters, interleave]) -> int[6], None -> NULL (the table's entry)."""
+    """(K, VPL, R, per_cu[, clusters, interleave, flat]) -> int[7], None -> NULL (the table's entry)."""
     if shape is None:
         return None
-    vals = [int(v) for v in shape] + [0, 0]
-    return (ctypes.c_int * 6)(*vals[:6])
+    vals = [int(v) for v in shape] + [0, 0, 0]
+    return (ctypes.c_int * 7)(*vals[:7])
 
 
 def _ptr_array(ts):

@@ -8,7 +8,7 @@
 #include "lnmod_tools.h"
 
 int main(void) {
-    int shape[6] = {0, 0, 0, 0, 0, 0};      /* K, VPL, R, per_cu, clusters, interleave */
+    int shape[7] = {0, 0, 0, 0, 0, 0, 0};   /* K, VPL, R, per_cu, clusters, interleave, flat */
     /* validation runs before any device call, so these work on a host without a GPU */
     if (lnmod_forward(NULL, NULL, NULL, 1, 8, 64, 1e-6f, NULL, NULL, NULL, NULL, LNMOD_BF16, LNMOD_PER_SAMPLE) !=
         LNMOD_EINVAL)

@@ -310,7 +310,7 @@ def sbwd(shape, dy=A, x=A, scale=A, cu=None, B=2, S=4, D=64, eps=1e-6, mean=A, r
 def test_shaped_calls_validate_the_shape_and_then_like_the_operator_calls(tools):
     E = lnmod
     for bad in ((17, 1, 1, 1), (-1, 1, 1, 1), (0, 1, 1, 1), (1, 0, 1, 1), (1, 7, 1, 1), (1, 1, 0, 1), (1, 1, 3, 1),
-                (1, 1, 1, 0), (1, 1, 1, 17), (1, 1, 1, 4, -1, 0), (1, 1, 1, 4, 257, 0), (1, 1, 1, 4, 8, 2)):
+                (1, 1, 1, 0), (1, 1, 1, 17), (1, 1, 1, 4, -1, 0), (1, 1, 1, 4, 257, 0), (1, 1, 1, 4, 8, 2), (1, 1, 1, 4, 0, 0, 3), (1, 1, 1, 4, 0, 0, -1)):
         assert sfwd(bad) == E.LNMOD_EINVAL, bad
         assert sbwd(bad) == E.LNMOD_EINVAL, bad
         assert T.lnmod_backward_workspace_bytes_shaped(bad, 1, 100, 64, 0) == 0
@@ -373,3 +373,26 @@ def test_describe_launch_names_the_kernels_of_the_headline_workload(tools):
     assert d(False, (5, 2, 2, 1, 8, 1), 1, 75600, False, 5120, 0, 0).endswith("grid=256 block=320 clusters=8")
     assert d(True, (4, 3, 2, 1, 8, 1), 1, 75600, False, 5120, 0, 0).endswith("slots=256")
     assert d(False, None, 1, 0, False, 5120, 0, 0) == "" and d(False, None, 1, 10, False, 5121, 0, 0) == ""
+
+
+def test_describe_launch_shows_which_forward_loop_a_batch_of_several_segments_gets(tools):
+    d = T.lnmod_describe_launch
+    # bf16 rows shared by three or more waves, and D = 1536: one loop over all rows (mode 4), the fewest
+    # clusters (a power of two, 2 ... 32) that leave a block at most 32 segments
+    assert d(False, None, 24, 152880, True, 5120, 0, 0) == \
+        "fwd_split_kernel<bf16_io, 2, 5, 2, true, 4, true> grid=256 block=320 clusters=2"
+    assert d(False, None, 96, 149760, True, 5120, 0, 0).endswith("4, true> grid=256 block=320 clusters=4")
+    assert d(False, None, 480, 149760, True, 5120, 0, 0).endswith("clusters=16")
+    assert d(False, None, 5000, 150000, True, 5120, 0, 0).endswith("clusters=32")
+    assert d(False, None, 4, 32760, False, 5120, 0, 0).endswith("4, true> grid=256 block=320 clusters=2")
+    assert d(False, None, 24, 152880, True, 1536, 0, 0) == \
+        "fwd_split_kernel<bf16_io, 3, 1, 2, true, 4, true> grid=1024 block=64 clusters=2"
+    # one segment, narrow bf16 rows and fp32: one loop per segment (mode 0)
+    assert ", 0, true>" in d(False, None, 1, 152880, True, 5120, 0, 0)
+    assert ", 0, true>" in d(False, None, 24, 152880, True, 2048, 0, 0)
+    assert ", 0, true>" in d(False, None, 24, 152880, True, 5120, 1, 0)
+    # shape[6] overrides the choice either way
+    tab = (5, 2, 2, 1)
+    assert ", 0, true>" in d(False, tab + (0, 0, 2), 24, 152880, True, 5120, 0, 0)
+    assert ", 4, true>" in d(False, (2, 2, 1, 4, 0, 0, 1), 24, 152880, True, 2048, 0, 0)
+    assert d(False, tab + (8, 1, 1), 24, 152880, True, 5120, 0, 0).endswith("4, true> grid=256 block=320 clusters=8")

@@ -81,6 +81,31 @@ def test_given_cluster_counts_and_block_interleaving_match_the_oracle(clusters, 
     run_shaped(synth.make_inputs(4, lengths=lengths), fwd, bwd, rc, "varlen, %d clusters" % clusters)
 
 
+@pytest.mark.parametrize("clusters", [0, 1, 2, 5, 64])
+def test_one_loop_over_all_rows_gives_the_forward_of_one_loop_per_segment_bit_for_bit(clusters):
+    # shape[6] = 1: the block's rows are taken whatever segment they fall in and the modulation registers
+    # are reloaded where the segment changes; = 2: one loop per segment.  Same shape, same row arithmetic.
+    lengths = (37, 0, 1560, 5, 819, 1, 0, 0, 300, 64, 2, 777, 0, 1, 1, 1, 2, 0, 3, 2049, 0)
+    for D, base in ((5120, (5, 2, 2, 1)), (5120, (4, 3, 1, 2)), (1536, (1, 3, 2, 4)), (1528, (1, 3, 2, 4))):
+        inp = synth.make_inputs(4, lengths=lengths, D=D, seed=11)
+        print("flat against per-segment", D, base, clusters, flush=True)
+        x = to_device(inp.x, "bf16")
+        shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+        cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+        outs = []
+        for flat in (1, 2):
+            st, y, mean, rstd = shaped_forward(base + (clusters, 1, flat), x, shift, scale, cu, inp.B, inp.T, D)
+            assert st == 0, lnmod.lnmod_status_string(st)
+            torch.cuda.synchronize()
+            outs.append((y, mean, rstd))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+        y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, inp.workload.eps,
+                                             cu=inp.cu_seqlens.astype(np.int64))
+        check_io_tensor("y", outs[0][0], y64, "bf16")
+        check_stats(outs[0][1], outs[0][2], mean64, rstd64)
+
+
 def test_uncompiled_shape_fails_and_no_shape_is_the_operator_librarys_launch():
     inp = synth.make_inputs(2, S=1000)
     assert inp.D == 5120
