@@ -94,6 +94,7 @@ void gated_fwd_kernel(const GatedFwdArgs a) {
     int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
     int buf = 0;
+    uint32_t turn = 0;                       // see take_turn
 
     while (r0 < r1) {
         int64_t m = find_segment(a.seg, r0);
@@ -140,9 +141,10 @@ void gated_fwd_kernel(const GatedFwdArgs a) {
         };
         const int64_t step = static_cast<int64_t>(a.nb) * R;
         u32x4 raw[2][R][VPL];
-        fetch(r0 + member * R, raw);
+        const int64_t first = take_turn<R>(turn, r0, stop, member, a.nb);
+        fetch(first, raw);
 
-        for (int64_t base = r0 + member * R; base < stop; base += step) {
+        for (int64_t base = first; base < stop; base += step) {
             u32x4 nxt[2][R][VPL];
             fetch(base + step, nxt);
             __builtin_amdgcn_sched_barrier(0);               // keep the requests up here
@@ -325,6 +327,7 @@ void gated_bwd_kernel(const GatedBwdArgs a) {
     int64_t r1 = r0 + a.rows_per_cluster;
     if (r1 > a.T) r1 = a.T;
     int buf = 0;
+    uint32_t turn = 0;                       // see take_turn
 
     while (r0 < r1) {
         const int64_t m = find_segment(a.seg, r0);
@@ -378,9 +381,10 @@ void gated_bwd_kernel(const GatedBwdArgs a) {
         const int64_t step = static_cast<int64_t>(a.nb) * R;
         u32x4 raw[NS][R][VPL];
         float mu[R], rs[R];
-        fetch(r0 + member * R, raw, mu, rs);
+        const int64_t first = take_turn<R>(turn, r0, stop, member, a.nb);
+        fetch(first, raw, mu, rs);
 
-        for (int64_t base = r0 + member * R; base < stop; base += step) {
+        for (int64_t base = first; base < stop; base += step) {
             u32x4 nxt[NS][R][VPL];
             float nmu[R], nrs[R];
             fetch(base + step, nxt, nmu, nrs);
