@@ -120,26 +120,35 @@ inline RowPlan plan_rows_clusters(int64_t T, int64_t nseg, int64_t max_blocks, i
 }
 
 // Fraction of the streaming time a backward launch loses when its blocks form C clusters, i.e.
-// move C windows through memory at once instead of one (measured at D = 5120 on 149 760 tokens
-// in equal segments, restarts taken out: 1.2, 2.9, 7.9, 12.4, 15.5 % at C = 2, 4, 8, 16, 32;
-// extrapolated beyond), interpolated in log2 C.
-inline double cluster_penalty(int64_t C) {
-    static const double tab[] = {0.0, 0.012, 0.029, 0.079, 0.124, 0.155, 0.19, 0.22, 0.25};
+// move C windows through memory at once instead of one, interpolated in log2 C.  Two measured
+// tables (equal segments of about 150 000 tokens in all, slots and restarts taken out): launches of
+// one block per CU (D = 5120, 256 blocks): 1.2, 2.2, 4.8, 10.7, 12.4 % at C = 2, 4, 8, 16, 32; launches
+// of several small blocks per CU (D = 1536, 768 blocks): 0, 0, 2, 5, 5.5 % and 12 % at C = 768;
+// extrapolated in between and beyond.
+inline double cluster_penalty(int64_t C, bool one_block_per_cu) {
+    static const double wide[] = {0.0, 0.012, 0.022, 0.048, 0.107, 0.124, 0.16, 0.20, 0.24, 0.27, 0.30};
+    static const double narrow[] = {0.0, 0.0, 0.0, 0.02, 0.05, 0.055, 0.07, 0.09, 0.10, 0.115, 0.13};
+    const double* tab = one_block_per_cu ? wide : narrow;
     if (C <= 1) return 0.0;
-    if (C >= 256) return tab[8];
+    if (C >= 1024) return tab[10];
     int lo = 0;
-    while ((int64_t{2} << lo) <= C) ++lo;                    // 2^lo <= C < 2^(lo+1), lo <= 7
+    while ((int64_t{2} << lo) <= C) ++lo;                    // 2^lo <= C < 2^(lo+1), lo <= 9
     const double frac = static_cast<double>(C - (int64_t{1} << lo)) / static_cast<double>(int64_t{1} << lo);
     return tab[lo] + (tab[lo + 1] - tab[lo]) * frac;
 }
 
 // Row plan of a backward that keeps per-(block, segment) partial-sum slots.  With several
 // segments the blocks per cluster nb (a power of two) minimise
-//     stream_us * cluster_penalty(C)                       windows
-//   + (C + nseg) * nb * slot_rows * stream_us / T          slots written and read back
-//   + (nseg / C + 1) * 4 us                                pipeline restarts per block
+//     stream_us * cluster_penalty(C)                              windows
+//   + max(0, (C + nseg) * nb * slot_rows * stream_us / T - 58 us)  slots written and read back
+//   + (nseg / C + 1) * 2 us (4 us with several blocks per CU)     pipeline restarts per block
+//   + (nseg - 1) * 8 us if C = 1                                  all blocks restart at once
 // where slot_rows is what one slot costs in units of one row's traffic and stream_us the time
-// the rows take at the streaming rate.
+// the rows take at the streaming rate.  The first 58 us of slot traffic are free: about 128 MB of
+// slots are still in the last-level cache when the second pass reads them (480 segments of 312
+// rows at D = 5120: 4088 slots of 41 KB cost 8 us together with the restarts, 15 584 slots 249 us).
+// A lone cluster pays for every boundary with the whole chip: all its blocks drain their
+// pipelines at the same moment (3 x 75 600 rows at D = 5120: 1233 us with one cluster, 1183 with two).
 inline RowPlan plan_rows_slots(int64_t T, int64_t nseg, int64_t max_blocks, int rows_per_step,
                                double stream_us, double slot_rows, int64_t forced = 0) {
     if (T <= 0) return RowPlan{0, 0, 1, 1};
@@ -149,18 +158,25 @@ inline RowPlan plan_rows_slots(int64_t T, int64_t nseg, int64_t max_blocks, int 
         nb = g / forced > 0 ? g / forced : 1;
     } else if (nseg > 1) {
         double best = 0.0;
-        for (int64_t cand = 1; cand <= g; cand *= 2) {
+        bool have = false;
+        for (int64_t cand = 1; cand < 2 * g; cand *= 2) {
+            if (cand > g) cand = g;                          // the last candidate: one cluster
             int64_t C = (g + cand - 1) / cand;
             const int64_t rpc = (T + C - 1) / C;
             C = (T + rpc - 1) / rpc;
-            const double cost = stream_us * cluster_penalty(C) +
-                                static_cast<double>(C + nseg) * static_cast<double>(cand) * slot_rows *
-                                    stream_us / static_cast<double>(T) +
-                                (static_cast<double>(nseg) / static_cast<double>(C) + 1.0) * 4.0;
-            if (cand == 1 || cost < best) {
+            double slots_us = static_cast<double>(C + nseg) * static_cast<double>(cand) * slot_rows * stream_us /
+                                  static_cast<double>(T) - 58.0;
+            if (slots_us < 0.0) slots_us = 0.0;
+            const bool one_per_cu = max_blocks <= kNumCU;
+            const double cost = stream_us * cluster_penalty(C, one_per_cu) + slots_us +
+                                (static_cast<double>(nseg) / static_cast<double>(C) + 1.0) * (one_per_cu ? 2.0 : 4.0) +
+                                (C == 1 ? static_cast<double>(nseg - 1) * 8.0 : 0.0);
+            if (!have || cost < best) {
+                have = true;
                 best = cost;
                 nb = cand;
             }
+            if (cand == g) break;
         }
     }
     return make_plan(T, g, nb);

@@ -61,9 +61,22 @@ int main() {
         const ReduceShape rs = reduce_shape(nseg, 2 + it % 2, 8 * (1 + static_cast<int64_t>(rng() % 1024)), ps.clusters, ps.nb);
         CHECK((rs.V == 1 || rs.V == 2 || rs.V == 4) && rs.W >= 1 && rs.W <= 16 && (rs.W & (rs.W - 1)) == 0, "reduce shape V %d W %d", rs.V, rs.W);
     }
-    for (int64_t C = 1; C < 2000; ++C) {
-        const double p = cluster_penalty(C), q = cluster_penalty(C + 1);
-        CHECK(p >= 0.0 && p <= 0.25 + 1e-12 && q + 1e-12 >= p, "cluster_penalty(%lld) = %g, next %g", (long long)C, p, q);
+    for (int wide = 0; wide < 2; ++wide) {
+        for (int64_t C = 1; C < 2000; ++C) {
+            const double p = cluster_penalty(C, wide != 0), q = cluster_penalty(C + 1, wide != 0);
+            CHECK(p >= 0.0 && p <= 0.30 + 1e-12 && q + 1e-12 >= p, "cluster_penalty(%lld) = %g, next %g", (long long)C, p, q);
+            CHECK(wide == 0 || p + 1e-12 >= cluster_penalty(C, false), "one block per CU pays less at %lld", (long long)C);
+        }
+    }
+    // the plans the cost model was fitted to (D = 5120: 256 blocks, rows of 30 KB traffic)
+    {
+        const struct { int64_t T, nseg, clusters; } fit[] = {{152880, 24, 4}, {152880, 8, 2}, {149760, 96, 8},
+                                                            {149760, 480, 32}, {226800, 3, 2}, {65520, 2, 2}};
+        for (const auto& f : fit) {
+            const RowPlan ps = plan_rows_slots(f.T, f.nseg, 256, 2, static_cast<double>(f.T) * 30720.0 / 5.8e6, 16.0 / 6.0);
+            CHECK(ps.clusters == f.clusters, "T %lld nseg %lld: %lld clusters, fitted %lld", (long long)f.T,
+                  (long long)f.nseg, (long long)ps.clusters, (long long)f.clusters);
+        }
     }
     std::printf("checked, %d failures\n", bad);
     return bad == 0 ? 0 : 1;
