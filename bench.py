@@ -318,7 +318,14 @@ def condition(torch, stream, step, group=8, tol=0.01, min_ms=100.0, cap_ms=300.0
             "first_group_ms_per_step": round(means[0], 4), "last_group_ms_per_step": round(means[-1], 4)}
 
 
-def _time_ms(torch, stream, fn, iters=20, warm=3):
+def _time_ms(torch, stream, fn, iters=20, warm=3, settle_ms=30.0):
+    """Mean time of `iters` calls of fn (events on the launch stream).  Before the warm-up the call is
+    repeated, untimed, until its rate has settled (see condition(); at least `settle_ms` of GPU time):
+    between two measurements of this file the host builds tensors, and a GPU left idle for some tens
+    of milliseconds drops its clocks (50 ms pauses cost the forward 26 %, and the 20 launches of a
+    measurement taken right after tensor setup ran 580 ... 530 us where the settled rate is 512)."""
+    if settle_ms > 0:
+        condition(torch, stream, fn, min_ms=settle_ms, cap_ms=250.0)
     for _ in range(warm):
         fn()
     a = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
