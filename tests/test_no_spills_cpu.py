@@ -18,7 +18,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 # template arguments as c++filt prints them: <io, VPL, K, R, EXACT, ...>
 MUST_NOT_SPILL = [
-    r"fwd_split_kernel<lnmod::bf16_io, 2, 5, 2, true, 0, true>",          # workloads [2], [4] forward
+    r"fwd_split_kernel<lnmod::bf16_io, 2, 5, 2, true, 0, true>",          # workload [2] forward
+    r"fwd_split_kernel<lnmod::bf16_io, 2, 5, 2, true, 4, true>",          # workload [4] forward (one loop over all rows)
+    r"fwd_split_kernel<lnmod::bf16_io, 3, 1, 2, true, 4, true>",          # the same at D = 1536
     r"fwd_split_kernel<lnmod::bf16_io, 3, 1, 2, true, 0, true>",          # workload [1] forward
     r"fwd_split_kernel<lnmod::bf16_io, 5, 2, 1, true, 1, true>",          # workload [3] forward (per token)
     r"fwd_split_kernel<lnmod::f32_io, 4, 5, 1, true, 0, true>",           # fp32 I/O, D = 5120
