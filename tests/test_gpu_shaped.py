@@ -106,6 +106,46 @@ def test_one_loop_over_all_rows_gives_the_forward_of_one_loop_per_segment_bit_fo
         check_stats(outs[0][1], outs[0][2], mean64, rstd64)
 
 
+def test_one_loop_over_all_rows_on_random_segment_tables():
+    # random tables with many empty and one-row segments, token counts below and above the grid, cluster
+    # regions that end inside, at and between segment boundaries: the two forward loops agree bit for bit
+    rng = np.random.default_rng(2024)
+    D = 1024
+    for case in range(24):
+        nseg = int(rng.integers(2, 70))
+        kind = case % 4
+        if kind == 0:
+            lengths = rng.integers(0, 4, size=nseg)                   # fewer rows than blocks
+        elif kind == 1:
+            lengths = rng.integers(0, 400, size=nseg) * (rng.random(nseg) < 0.5)
+        elif kind == 2:
+            lengths = np.full(nseg, 64)                               # boundaries on the step grid
+        else:
+            lengths = rng.integers(1, 3000, size=nseg) * (rng.random(nseg) < 0.3) + (rng.random(nseg) < 0.2)
+        lengths = [int(v) for v in lengths]
+        if sum(lengths) == 0:
+            lengths[nseg // 2] = 1
+        clusters = int(rng.choice([0, 1, 2, 3, 8, 32, 256]))
+        base = [(1, 2, 2, 4), (2, 2, 1, 4), (1, 2, 1, 8)][case % 3]
+        print("random table", case, "nseg", nseg, "T", sum(lengths), "clusters", clusters, base, flush=True)
+        inp = synth.make_inputs(4, lengths=lengths, D=D, seed=100 + case, with_dy=False)
+        x = to_device(inp.x, "bf16")
+        shift, scale = to_device(inp.shift, "bf16"), to_device(inp.scale, "bf16")
+        cu = torch.from_numpy(inp.cu_seqlens.astype(np.int32)).cuda()
+        outs = []
+        for flat in (1, 2):
+            st, y, mean, rstd = shaped_forward(base + (clusters, int(case % 2), flat), x, shift, scale, cu, inp.B, inp.T, D)
+            assert st == 0, lnmod.lnmod_status_string(st)
+            torch.cuda.synchronize()
+            outs.append((y, mean, rstd))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+        y64, mean64, rstd64 = oracle.forward(inp.x, inp.shift, inp.scale, inp.workload.eps,
+                                             cu=inp.cu_seqlens.astype(np.int64))
+        check_io_tensor("y", outs[0][0], y64, "bf16")
+        check_stats(outs[0][1], outs[0][2], mean64, rstd64)
+
+
 def test_uncompiled_shape_fails_and_no_shape_is_the_operator_librarys_launch():
     inp = synth.make_inputs(2, S=1000)
     assert inp.D == 5120
