@@ -116,14 +116,17 @@ constexpr int64_t kReduceMaxGrid = int64_t(1) << 20;
 
 hipError_t launch_reduce(ReduceArgs r, int64_t clusters, hipStream_t st) {
     const ReduceShape sh = reduce_shape(r.seg.nseg, r.nsum, r.D, clusters, r.nb);
-    const int V = sh.V, W = sh.W;
-    r.dblocks = static_cast<int32_t>((r.D + kWave * V - 1) / (kWave * V));
+    const int V = sh.V, W = sh.W, G = sh.G;
+    const int per_block = kWave / G * V;
+    r.dblocks = static_cast<int32_t>((r.D + per_block - 1) / per_block);
     r.total = r.seg.nseg * r.nsum * r.dblocks;
     const int64_t g = r.total < kReduceMaxGrid ? r.total : kReduceMaxGrid;
     const dim3 grid(static_cast<unsigned>(g)), block(W * kWave);
-    if (V == 4) hipLaunchKernelGGL(bwd_reduce_kernel<4>, grid, block, 0, st, r);
-    else if (V == 2) hipLaunchKernelGGL(bwd_reduce_kernel<2>, grid, block, 0, st, r);
-    else hipLaunchKernelGGL(bwd_reduce_kernel<1>, grid, block, 0, st, r);
+    if (G == 4) hipLaunchKernelGGL((bwd_reduce_kernel<4, 4>), grid, block, 0, st, r);
+    else if (G == 2) hipLaunchKernelGGL((bwd_reduce_kernel<4, 2>), grid, block, 0, st, r);
+    else if (V == 4) hipLaunchKernelGGL((bwd_reduce_kernel<4, 1>), grid, block, 0, st, r);
+    else if (V == 2) hipLaunchKernelGGL((bwd_reduce_kernel<2, 1>), grid, block, 0, st, r);
+    else hipLaunchKernelGGL((bwd_reduce_kernel<1, 1>), grid, block, 0, st, r);
     return hipGetLastError();
 }
 
@@ -223,8 +226,9 @@ int describe_bwd(const Problem& p, bool per_token, bool recompute, char* buf, si
                           static_cast<long long>(L.pl.clusters));
     if (!per_token && k > 0 && static_cast<size_t>(k) < n) {
         const ReduceShape rs = reduce_shape(p.nseg, 2, p.D, L.pl.clusters, L.pl.nb);
-        const int64_t dblocks = (p.D + kWave * rs.V - 1) / (kWave * rs.V);
-        k += std::snprintf(buf + k, n - k, " + bwd_reduce_kernel<%d> grid=%lld block=%d slots=%lld", rs.V,
+        const int64_t per_block = kWave / rs.G * rs.V;
+        const int64_t dblocks = (p.D + per_block - 1) / per_block;
+        k += std::snprintf(buf + k, n - k, " + bwd_reduce_kernel<%d, %d> grid=%lld block=%d slots=%lld", rs.V, rs.G,
                            static_cast<long long>(p.nseg * 2 * dblocks), rs.W * kWave,
                            static_cast<long long>(bwd_slots(L.pl, p.nseg)));
     }

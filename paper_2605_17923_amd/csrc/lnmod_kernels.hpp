@@ -946,16 +946,18 @@ template <> struct FVec<1> { typedef float type; };
 // Block b takes the triples b, b + gridDim.x, ... below a.total, each decoded as (segment, which
 // sum, block of 64 * V features); the grid is min(total, a bound), so that any segment count the
 // interface admits stays inside the launch limits.
-template <int V>
+template <int V, int G = 1>
 __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const ReduceArgs a) {
     using vec = typename FVec<V>::type;
     constexpr int kReduceBatch = kReduceFloats / V;
-    __shared__ vec red[kReduceWaves][kWave];
+    constexpr int FL = kWave / G;                 // lanes along the features; G groups of them take different slots
+    __shared__ vec red[kReduceWaves][FL];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int W = blockDim.x >> 6;
+    const int fl = lane % FL, grp = lane / FL;
     for (int64_t bid = blockIdx.x; bid < a.total; bid += gridDim.x) {
-        const int d = (static_cast<int>(bid % a.dblocks) * kWave + lane) * V;
+        const int d = (static_cast<int>(bid % a.dblocks) * FL + fl) * V;
         const int which = static_cast<int>((bid / a.dblocks) % a.nsum);
         const int64_t m = bid / (static_cast<int64_t>(a.nsum) * a.dblocks);
         int64_t n0 = seg_begin(a.seg, m), n1 = seg_begin(a.seg, m + 1);
@@ -968,29 +970,42 @@ __global__ __launch_bounds__(kReduceWaves* kWave) void bwd_reduce_kernel(const R
             const int64_t s_lo = (c_lo + m) * a.nb, s_hi = (c_hi + m + 1) * a.nb;
             const float* base = a.ws + static_cast<int64_t>(which) * a.D + d;
             const int64_t pitch = static_cast<int64_t>(a.nsum) * a.D;
+            const int64_t stride = static_cast<int64_t>(W) * G;
             // kReduceBatch slots requested before the first is added (the chain of dependent round
             // trips, not the bytes, is what this kernel's time consists of); the additions keep slot order
-            for (int64_t sl = s_lo + wave; sl < s_hi; sl += kReduceBatch * W) {
+            for (int64_t sl = s_lo + wave * G + grp; sl < s_hi; sl += kReduceBatch * stride) {
                 vec v[kReduceBatch];
 #pragma unroll
                 for (int u = 0; u < kReduceBatch; ++u) {
-                    const int64_t su = sl + static_cast<int64_t>(u) * W;
+                    const int64_t su = sl + static_cast<int64_t>(u) * stride;
                     v[u] = su < s_hi ? *reinterpret_cast<const vec*>(base + su * pitch) : vec(0.0f);
                 }
 #pragma unroll
                 for (int u = 0; u < kReduceBatch; ++u) acc += v[u];
             }
         }
+        if constexpr (G > 1) {
+            // the G groups of the wave, in a fixed order
+#pragma unroll
+            for (int off = FL; off < kWave; off <<= 1) {
+                if constexpr (V == 1) {
+                    acc += __shfl_xor(acc, off);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) acc[e] += __shfl_xor(acc[e], off);
+                }
+            }
+        }
         if (W > 1) {
-            red[wave][lane] = acc;
+            if (grp == 0) red[wave][fl] = acc;
             __syncthreads();
-            if (wave == 0) {
-                acc = red[0][lane];
-                for (int w = 1; w < W; ++w) acc += red[w][lane];
+            if (wave == 0 && grp == 0) {
+                acc = red[0][fl];
+                for (int w = 1; w < W; ++w) acc += red[w][fl];
             }
             __syncthreads();                      // red is written again in the next round
         }
-        if (wave == 0 && d < a.D)
+        if (wave == 0 && grp == 0 && d < a.D)
             *reinterpret_cast<vec*>(a.out[which] + m * a.D + d) = acc;
     }
 }

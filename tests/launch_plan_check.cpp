@@ -60,6 +60,7 @@ int main() {
         if (nseg == 1) CHECK(ps.clusters == 1, "one segment wants one cluster, got %lld", (long long)ps.clusters);
         const ReduceShape rs = reduce_shape(nseg, 2 + it % 2, 8 * (1 + static_cast<int64_t>(rng() % 1024)), ps.clusters, ps.nb);
         CHECK((rs.V == 1 || rs.V == 2 || rs.V == 4) && rs.W >= 1 && rs.W <= 16 && (rs.W & (rs.W - 1)) == 0, "reduce shape V %d W %d", rs.V, rs.W);
+        CHECK((rs.G == 1 || rs.G == 2 || rs.G == 4) && (rs.G == 1 || rs.V == 4), "reduce shape V %d G %d", rs.V, rs.G);
     }
     for (int wide = 0; wide < 2; ++wide) {
         for (int64_t C = 1; C < 2000; ++C) {

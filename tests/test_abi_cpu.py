@@ -365,7 +365,7 @@ def test_describe_launch_names_the_kernels_of_the_headline_workload(tools):
         "fwd_split_kernel<bf16_io, 2, 5, 2, true, 0, true> grid=256 block=320 clusters=1"
     assert d(True, None, 1, 75600, False, 5120, 0, 0) == \
         ("bwd_seg_kernel<bf16_io, 3, 4, 2, false, false, true, false> grid=256 block=256 clusters=1"
-         " + bwd_reduce_kernel<1> grid=160 block=1024 slots=256")
+         " + bwd_reduce_kernel<4, 4> grid=160 block=1024 slots=256")
     assert "true, true>" in d(True, None, 1, 75600, False, 5120, 0, 0, recompute=True)
     assert d(True, None, 2, 32760, False, 5120, 0, 1).startswith("bwd_seg_kernel<bf16_io, 2, 5, 1, true, true, true, false>")
     assert "reduce" not in d(True, None, 2, 32760, False, 5120, 0, 1)

@@ -28,7 +28,8 @@ MUST_NOT_SPILL = [
     r"bwd_seg_kernel<lnmod::bf16_io, 3, 4, 1, false, false, true, true>",   # the same without saved statistics
     r"bwd_seg_kernel<lnmod::bf16_io, 1, 3, 1, true, false, true, false>",   # D = 1536 backward
     r"bwd_seg_kernel<lnmod::bf16_io, 2, 5, 1, true, true, true, false>",    # workload [3] backward (per token)
-    r"bwd_reduce_kernel<1>", r"bwd_reduce_kernel<2>", r"bwd_reduce_kernel<4>",
+    r"bwd_reduce_kernel<4, 4>", r"bwd_reduce_kernel<4, 2>", r"bwd_reduce_kernel<4, 1>",
+    r"bwd_reduce_kernel<2, 1>", r"bwd_reduce_kernel<1, 1>",
 ]
 
 
