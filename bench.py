@@ -526,8 +526,8 @@ def _run_qknorm(lnmod, torch, stream, st, dev, T, D, iters=20):
 def probe_ceilings(lnmod_tools, torch, stream, st, bufs, nbytes):
     """What the memory system gives to the read/write mixtures of the kernels, in the copy's access
     pattern: GB/s of lnmod_stream_probe for (reads, writes) streams of `nbytes` each.  The mixtures:
-    reads alone, writes alone, 1R1W (forward), 2R1W (backward), 3R1W (per-token forward), 3R3W
-    (per-token backward), 4R2W (gated backward)."""
+    reads alone, writes alone, 1R1W (forward), 2R1W (backward), 2R2W (gated forward, Q/K-norm forward),
+    3R1W (per-token forward), 3R3W (per-token backward), 4R2W (gated backward, Q/K-norm backward)."""
     res = {}
     for nr, nw in lnmod_tools.PROBE_MIXTURES:
         ins = bufs[:nr]

@@ -38,7 +38,7 @@ int lnmod_copy(const void* src, void* dst, size_t bytes, void* stream);
  * bytes each (a multiple of 16; a tail shorter than one piece of 4 or 8 KB is left out).  Every
  * output is the 32-bit-lane sum of the inputs plus j (a position-dependent pattern when reads is 0).
  * With writes == 0 the inputs are read and summed, and out[0] must point to 1 KB that is normally
- * not written.  Supported (reads, writes): (1,0) (0,1) (1,1) (2,1) (3,1) (3,3) (4,2).
+ * not written.  Supported (reads, writes): (1,0) (0,1) (1,1) (2,1) (2,2) (3,1) (3,3) (4,2).
  * blocks, waves (per block, 1..8) and vecs (16-byte vectors per lane and step: 1, 2, 4 or 8) give
  * the launch; all three 0 selects the mixture's default (the best of a sweep).
  * LNMOD_EINVAL for any other mixture or launch, a NULL pointer or bytes not a multiple of 16.

@@ -38,7 +38,7 @@ bool go_probe(const ProbeArgs& a, int blocks, int waves, int vecs, hipStream_t s
 
 bool probe_mixture_supported(int reads, int writes) {
     const int key = reads * 10 + writes;
-    return key == 10 || key == 1 || key == 11 || key == 21 || key == 31 || key == 33 || key == 42;
+    return key == 10 || key == 1 || key == 11 || key == 21 || key == 22 || key == 31 || key == 33 || key == 42;
 }
 
 hipError_t launch_stream_probe(const void* const* in, int reads, void* const* out, int writes, size_t bytes,
@@ -52,6 +52,7 @@ hipError_t launch_stream_probe(const void* const* in, int reads, void* const* ou
     if (blocks <= 0 || waves <= 0 || vecs <= 0) {
         if (key == 10) { blocks = 2 * kNumCU; waves = 4; vecs = 4; }
         else if (key == 1) { blocks = kNumCU / 2; waves = 1; vecs = 8; }
+        else if (key == 22) { blocks = kNumCU; waves = 2; vecs = 8; }
         else { blocks = kNumCU; waves = 4; vecs = 4; }
     }
     if (waves > 8 || blocks > 65536) return hipErrorInvalidConfiguration;
@@ -61,6 +62,7 @@ hipError_t launch_stream_probe(const void* const* in, int reads, void* const* ou
         case 1: ok = go_probe<0, 1>(a, blocks, waves, vecs, st); break;
         case 11: ok = go_probe<1, 1>(a, blocks, waves, vecs, st); break;
         case 21: ok = go_probe<2, 1>(a, blocks, waves, vecs, st); break;
+        case 22: ok = go_probe<2, 2>(a, blocks, waves, vecs, st); break;
         case 31: ok = go_probe<3, 1>(a, blocks, waves, vecs, st); break;
         case 33: ok = go_probe<3, 3>(a, blocks, waves, vecs, st); break;
         case 42: ok = go_probe<4, 2>(a, blocks, waves, vecs, st); break;

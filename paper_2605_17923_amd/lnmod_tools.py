@@ -24,7 +24,7 @@ EXPORTS = ("lnmod_copy", "lnmod_stream_probe", "lnmod_unfused_forward", "lnmod_g
 LNMOD_FAMILIES = 9
 
 # read/write mixtures lnmod_stream_probe is compiled for
-PROBE_MIXTURES = ((1, 0), (0, 1), (1, 1), (2, 1), (3, 1), (3, 3), (4, 2))
+PROBE_MIXTURES = ((1, 0), (0, 1), (1, 1), (2, 1), (2, 2), (3, 1), (3, 3), (4, 2))
 
 _lib = None
 

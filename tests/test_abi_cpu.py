@@ -276,7 +276,7 @@ def test_copy_probe_and_comparators_reject_bad_arguments(tools):
     assert T.lnmod_copy(A, A, 0, None) == E.LNMOD_OK
     probe = T.lnmod_stream_probe
     assert probe([A, A, A, A, A], [A], 4096, None) == E.LNMOD_EINVAL           # no such mixture
-    assert probe([A, A], [A, A], 4096, None) == E.LNMOD_EINVAL
+    assert probe([A, A, A, A], [A], 4096, None) == E.LNMOD_EINVAL
     assert probe([A, None], [A], 4096, None) == E.LNMOD_EINVAL
     assert probe([A], [None], 4096, None, writes=0) == E.LNMOD_EINVAL
     assert probe([A], [A], 512, None, writes=0) == E.LNMOD_EINVAL             # out[0] must hold 1 KB
