@@ -52,7 +52,7 @@ hipError_t launch_stream_probe(const void* const* in, int reads, void* const* ou
     if (blocks <= 0 || waves <= 0 || vecs <= 0) {
         if (key == 10) { blocks = 2 * kNumCU; waves = 4; vecs = 4; }
         else if (key == 1) { blocks = kNumCU / 2; waves = 1; vecs = 8; }
-        else if (key == 22) { blocks = kNumCU; waves = 2; vecs = 8; }
+        else if (key == 22) { blocks = kNumCU; waves = 2; vecs = 4; }
         else { blocks = kNumCU; waves = 4; vecs = 4; }
     }
     if (waves > 8 || blocks > 65536) return hipErrorInvalidConfiguration;
