@@ -54,22 +54,25 @@ struct RowPlan {
     int32_t nb;
 };
 
-// Clusters a forward launch should at least use when the batch has several segments.  Every
-// block restarts its software pipeline once per segment of its cluster's region (about 2.2 us:
-// the modulation rows, then the first rows, arrive with nothing else in flight), so one cluster
-// walking 24 segments loses 55 us; more clusters mean fewer segments per block, but more than
-// four concurrent windows cost bandwidth.  The count that minimises
-//     stream_us * penalty(C) + (nseg / C + 1) * 2.2 us,   penalty = 1, 1, 1.01, 1.03, 1.06
-// over C = 1, 2, 4, 8, 16 is taken, a larger C only if it wins by 2 % (measured on 24 mixed
-// segments of D = 5120: 586, 553, 547, 555 us for C = 1, 2, 4, 8; on 96 segments of 1560 tokens
-// 600 us at C = 4 against 566 at C = 8).
+// Clusters a forward launch with one loop per segment should use when the batch has several
+// segments.  Every block restarts its software pipeline once per segment of its cluster's region
+// (about 2.2 us: the modulation rows, then the first rows, arrive with nothing else in flight), so
+// more clusters mean fewer segments per block, but concurrent windows cost bandwidth.  The count
+// that minimises
+//     stream_us * penalty(C) + (nseg / C + 1) * 2.2 us,   penalty = 1, 1.01, 1.03, 1.06, 1.10
+// over C = 2, 4, 8, 16, 32 is taken, a larger C only if it wins by 2 %.  A batch of several segments
+// never gets a single cluster: all its blocks would reach every boundary at the same moment and
+// the whole chip would drain (fp32, D = 5120, 8 equal segments: 566 us with one cluster, 541 with
+// two, 535 with four).  Measured with 2 ... 32 clusters on 24 mixed, 8, 96 and 480 equal segments
+// at D = 512 ... 2048 bf16 and D = 1536, 5120 fp32: the choice is within 3 % of the best count
+// except on 96 segments at D = 2048 (231 us against 221 with eight clusters).
 inline int64_t pick_clusters(double stream_us, int64_t nseg) {
     if (nseg <= 1) return 1;
-    const int c[] = {1, 2, 4, 8, 16};
-    const double penalty[] = {1.0, 1.0, 1.01, 1.03, 1.06};
-    int64_t best = 1;
+    const int c[] = {2, 4, 8, 16, 32};
+    const double penalty[] = {1.0, 1.01, 1.03, 1.06, 1.10};
+    int64_t best = 2;
     double best_t = 0.0;
-    for (int i = 0; i < 5 && c[i] <= nseg; ++i) {
+    for (int i = 0; i < 5 && (i == 0 || c[i] <= nseg); ++i) {
         const double t = stream_us * penalty[i] + (static_cast<double>(nseg) / c[i] + 1.0) * 2.2;
         if (i == 0 || t < best_t * 0.98) {
             best = c[i];

@@ -51,7 +51,7 @@ int main() {
         check_plan("plan_rows", plan_rows(T, max_blocks, R), T, g);
         const double stream_us = static_cast<double>(T) * 30720.0 / 5.8e6;
         const int64_t want = pick_clusters(stream_us, nseg);
-        CHECK(want >= 1 && want <= 16 && (want <= nseg || want == 1), "pick_clusters %lld for %lld segments", (long long)want, (long long)nseg);
+        CHECK(want >= 1 && want <= 32 && (want <= nseg || want <= 2) && (nseg == 1) == (want == 1), "pick_clusters %lld for %lld segments", (long long)want, (long long)nseg);
         check_plan("plan_rows_clusters", plan_rows_clusters(T, nseg, max_blocks, R, want), T, g);
         const RowPlan ps = plan_rows_slots(T, nseg, max_blocks, R, stream_us, 16.0 / 6.0);
         check_plan("plan_rows_slots", ps, T, g);
