@@ -143,6 +143,20 @@ def test_many_samples_fixed_length():
     run_case(synth.make_inputs(0, B=33, S=50, D=5120, dtype="f32"), label="fp32 B=33 S=50 D=5120")
 
 
+@pytest.mark.parametrize("B,D,dtype", [(1, 5120, "bf16"), (4, 5120, "bf16"), (8, 5120, "bf16"), (2, 1536, "bf16"),
+                                       (1, 1028, "f32"), (3, 8192, "f32")])
+def test_second_pass_shapes(B, D, dtype):
+    # the three forms of the second pass at D = 5120: one segment (64 features per block, four groups of
+    # lanes on different slots), four segments (128 features, two groups), eight (256 features, one
+    # group); D = 1536 and fp32 rows, one of them not a multiple of a block's width
+    expect = {(1, 5120): "<4, 4>", (4, 5120): "<4, 2>", (8, 5120): "<4, 1>"}.get((B, D))
+    if expect is not None:
+        from paper_2605_17923_amd import lnmod_tools
+        assert "bwd_reduce_kernel" + expect in lnmod_tools.lnmod_describe_launch(True, None, B, 300, False, D, 0, 0)
+    run_case(synth.make_inputs(2 if dtype == "bf16" else 0, B=B, S=300, D=D, dtype=dtype),
+             label="second pass B=%d D=%d %s" % (B, D, dtype))
+
+
 def test_malformed_segment_table_stays_in_bounds():
     # the table is only read on the device; whatever it holds, no access may leave the buffers.
     # Afterwards a well-formed call must still be right.
